@@ -1,0 +1,235 @@
+"""CPU oracle for the OAPL trainer-step loss head (fp64, numpy).
+
+TEST INFRASTRUCTURE ONLY.  This file is the plain, slow statement of what the
+GPU library must compute.  It is imported by the tests, by the smoke check and
+by the benchmark's CPU-baseline leg, and by nothing else; it shares no code,
+tables or helpers with the HIP path and never calls it.
+
+What it computes, in the paper's order and notation:
+
+* the per-token log-probability of the sampled token under the trainer policy
+  pi, ln pi(y_t | x, y_<t), with pi the soft-max over the full vocabulary of
+  the LM-head logits z_t = W h_t at temperature 1 (Sec. 2; generation settings
+  in the appendix use temperature 1 and top-p 1);
+* the sequence log-ratio ln pi(y|x) - ln pi_vllm(y|x) as the plain sum over the
+  rollout's tokens (Eq. 3 is written at sequence level and carries no length
+  normalisation);
+* the group value estimate V*(x) = beta ln (1/G) sum_i exp(r(x, y_i) / beta)
+  (Sec. 3.1, Eq. 2);
+* the OAPL objective sum_x sum_i (beta ln(pi/pi_vllm) - (r - V*))^2
+  (Sec. 3.1, Eq. 3), a plain sum of squares with no ratios and no clipping;
+* its gradient with respect to the hidden states H and the LM-head weights W
+  by the chain rule, with V* and the inference log-probs held constant (V* is
+  a function of rewards only).
+
+All floating point is float64 except the value estimate, which evaluates
+Eq. 2 literally in 50-digit arithmetic so that exp(r / beta) cannot overflow
+for the small betas the paper's experiments use.  Dense contractions are
+``numpy.matmul`` calls; rows are processed in slabs only to bound memory (every
+token row is independent).  There is no tiling, no online merging and no
+reordering of the definitions.
+
+Pins (tests/test_oracle_pins.py): brute-force soft-max on tiny vocabularies in
+50-digit arithmetic, W = 0 giving -ln V, shift and permutation invariances,
+scipy's log_softmax and logsumexp, the beta -> 0 / beta -> infinity limits of
+Eq. 2, the all-equal-rewards closed form V* = r, the binary-reward closed form,
+the pi = pi_vllm closed form of Eq. 3, the constructed minimiser of Eq. 3
+(loss 0, gradient 0), and central finite differences for every element of dH
+and dW.  No value the paper prints exists for this path (it prints no worked
+example), so full-size numbers are pinned by these properties only.
+"""
+from __future__ import annotations
+
+import numpy as np
+import mpmath
+
+_MP_DIGITS = 50
+
+
+def _f64(a) -> np.ndarray:
+    return np.ascontiguousarray(np.asarray(a, dtype=np.float64))
+
+
+# --------------------------------------------------------------------------
+# Per-token log-probabilities (soft-max over the full vocabulary, Sec. 2)
+# --------------------------------------------------------------------------
+
+def logits(H, W) -> np.ndarray:
+    """z[t, v] = sum_k H[t, k] W[v, k]."""
+    return _f64(H) @ _f64(W).T
+
+
+def log_softmax_rows(z: np.ndarray):
+    """Two-pass log-soft-max of each row: returns (log p, lse)."""
+    m = z.max(axis=1, keepdims=True)
+    lse = m + np.log(np.exp(z - m).sum(axis=1, keepdims=True))
+    return z - lse, lse[:, 0]
+
+
+def token_logprobs(H, W, tokens, rows=None, slab: int = 256):
+    """ln pi(y_t | .) and the log-partition lse_t for the selected token rows.
+
+    ``rows`` (optional) is an index array into the packed token stream; the
+    result is aligned with it.  Returns (lp, lse), both float64.
+    """
+    W64 = _f64(W)
+    tokens = np.asarray(tokens).astype(np.int64)
+    if rows is None:
+        rows = np.arange(np.asarray(H).shape[0])
+    rows = np.asarray(rows, dtype=np.int64)
+    if tokens.size and (tokens[rows].min() < 0 or tokens[rows].max() >= W64.shape[0]):
+        raise ValueError("sampled token outside [0, V)")
+    lp = np.empty(rows.size, dtype=np.float64)
+    lse = np.empty(rows.size, dtype=np.float64)
+    for a in range(0, rows.size, slab):
+        r = rows[a:a + slab]
+        z = _f64(np.asarray(H)[r]) @ W64.T
+        logp, l = log_softmax_rows(z)
+        lp[a:a + r.size] = logp[np.arange(r.size), tokens[r]]
+        lse[a:a + r.size] = l
+    return lp, lse
+
+
+# --------------------------------------------------------------------------
+# Sequence log-ratio (Eq. 3, the ln pi(y|x) / pi_vllm(y|x) term)
+# --------------------------------------------------------------------------
+
+def check_offsets(seq_offsets, T: int) -> np.ndarray:
+    off = np.asarray(seq_offsets).astype(np.int64)
+    if off.ndim != 1 or off.size < 1 or off[0] != 0 or off[-1] != T or np.any(np.diff(off) < 0):
+        raise ValueError("seq_offsets must start at 0, end at T and be non-decreasing")
+    return off
+
+
+def sequence_logratio(lp, logq, seq_offsets) -> np.ndarray:
+    """Delta_s = sum over the tokens of rollout s of (ln pi(y_t) - ln pi_vllm(y_t))."""
+    lp = _f64(lp)
+    logq = _f64(logq)
+    off = check_offsets(seq_offsets, lp.shape[0])
+    out = np.zeros(off.size - 1, dtype=np.float64)
+    for s in range(off.size - 1):
+        a, b = int(off[s]), int(off[s + 1])
+        out[s] = float(np.sum(lp[a:b] - logq[a:b]))
+    return out
+
+
+# --------------------------------------------------------------------------
+# Group value estimate (Eq. 2)
+# --------------------------------------------------------------------------
+
+def group_value_estimate(rewards, group_ids, n_groups: int, beta: float) -> np.ndarray:
+    """V*(x) = beta ln( (1/G) sum_{i=1..G} exp(r(x, y_i) / beta) ) per prompt.
+
+    Evaluated exactly as written, in 50-digit arithmetic.  G is the number of
+    rollouts that carry the prompt's group id.
+    """
+    rewards = _f64(rewards)
+    gid = np.asarray(group_ids).astype(np.int64)
+    if beta <= 0 or not np.isfinite(beta):
+        raise ValueError("beta must be positive and finite")
+    if gid.size and (gid.min() < 0 or gid.max() >= n_groups):
+        raise ValueError("group id outside [0, n_groups)")
+    out = np.empty(n_groups, dtype=np.float64)
+    with mpmath.workdps(_MP_DIGITS):
+        b = mpmath.mpf(float(beta))
+        for g in range(n_groups):
+            r = rewards[gid == g]
+            if r.size == 0:
+                raise ValueError(f"group {g} has no rollouts")
+            acc = mpmath.mpf(0)
+            for ri in r:
+                acc += mpmath.exp(mpmath.mpf(float(ri)) / b)
+            out[g] = float(b * mpmath.log(acc / r.size))
+    return out
+
+
+# --------------------------------------------------------------------------
+# Objective (Eq. 3) and its gradient
+# --------------------------------------------------------------------------
+
+def oapl_residuals(seq_logratio, rewards, group_ids, n_groups: int, beta: float,
+                   beta_value: float | None = None):
+    """delta_s = beta * Delta_s - (r_s - V*(x_s)).
+
+    ``beta`` is the coefficient of Eq. 3.  ``beta_value`` is the coefficient of
+    Eq. 2; it defaults to ``beta`` (the method section uses one constant; the
+    experimental section allows two).
+    Returns (delta, vstar).
+    """
+    vstar = group_value_estimate(rewards, group_ids, n_groups,
+                                 beta if beta_value is None else beta_value)
+    gid = np.asarray(group_ids).astype(np.int64)
+    adv = _f64(rewards) - vstar[gid]
+    delta = float(beta) * _f64(seq_logratio) - adv
+    return delta, vstar
+
+
+def oapl_loss(seq_logratio, rewards, group_ids, n_groups: int, beta: float,
+              beta_value: float | None = None, loss_scale: float = 1.0):
+    """Eq. 3: loss_scale * sum_s delta_s^2.  Returns (loss, delta, vstar)."""
+    delta, vstar = oapl_residuals(seq_logratio, rewards, group_ids, n_groups, beta, beta_value)
+    return float(loss_scale) * float(np.sum(delta * delta)), delta, vstar
+
+
+def token_coefficients(delta, seq_offsets, beta: float, loss_scale: float = 1.0) -> np.ndarray:
+    """c_t = dL / d ln pi(y_t) = loss_scale * 2 * beta * delta_{s(t)}."""
+    off = np.asarray(seq_offsets).astype(np.int64)
+    c = np.zeros(int(off[-1]), dtype=np.float64)
+    for s in range(off.size - 1):
+        c[int(off[s]):int(off[s + 1])] = float(loss_scale) * 2.0 * float(beta) * delta[s]
+    return c
+
+
+def grad_hidden_rows(H, W, tokens, coeff, rows, slab: int = 256) -> np.ndarray:
+    """dL/dH for the selected rows: c_t * (W[y_t, :] - sum_v p_{t,v} W[v, :])."""
+    W64 = _f64(W)
+    tokens = np.asarray(tokens).astype(np.int64)
+    rows = np.asarray(rows, dtype=np.int64)
+    coeff = _f64(coeff)
+    out = np.empty((rows.size, W64.shape[1]), dtype=np.float64)
+    for a in range(0, rows.size, slab):
+        r = rows[a:a + slab]
+        z = _f64(np.asarray(H)[r]) @ W64.T
+        logp, _ = log_softmax_rows(z)
+        p = np.exp(logp)
+        out[a:a + r.size] = coeff[r, None] * (W64[tokens[r]] - p @ W64)
+    return out
+
+
+def oapl_forward_backward(H, W, tokens, logq, seq_offsets, rewards, group_ids,
+                          n_groups: int, beta: float, beta_value: float | None = None,
+                          loss_scale: float = 1.0, backward: bool = True, slab: int = 256):
+    """The whole path on one batch.  Returns a dict of float64 results.
+
+    keys: logprob [T], lse [T], seq_logratio [N], vstar [P], delta [N], loss,
+    and with ``backward``: coeff [T], dH [T, d], dW [V, d].
+    """
+    H64 = _f64(H)
+    W64 = _f64(W)
+    T, d = H64.shape
+    V = W64.shape[0]
+    tokens = np.asarray(tokens).astype(np.int64)
+    off = check_offsets(seq_offsets, T)
+
+    lp, lse = token_logprobs(H64, W64, tokens, slab=slab)
+    Delta = sequence_logratio(lp, logq, off)
+    loss, delta, vstar = oapl_loss(Delta, rewards, group_ids, n_groups, beta, beta_value, loss_scale)
+    res = dict(logprob=lp, lse=lse, seq_logratio=Delta, vstar=vstar, delta=delta, loss=loss)
+    if not backward:
+        return res
+
+    c = token_coefficients(delta, off, beta, loss_scale)
+    dH = np.empty((T, d), dtype=np.float64)
+    dW = np.zeros((V, d), dtype=np.float64)
+    for a in range(0, T, slab):
+        b = min(T, a + slab)
+        z = H64[a:b] @ W64.T
+        p = np.exp(z - lse[a:b, None])
+        # dL/dz[t, v] = c_t * (1[v == y_t] - p[t, v])
+        dZ = -p
+        dZ[np.arange(b - a), tokens[a:b]] += 1.0
+        dZ *= c[a:b, None]
+        dH[a:b] = dZ @ W64
+        dW += dZ.T @ H64[a:b]
+    res.update(coeff=c, dH=dH, dW=dW)
+    return res
