@@ -1,0 +1,156 @@
+#!/usr/bin/env python3
+"""Throughput of the OAPL loss head on one MI355X.
+
+A step is one pass of the whole hot path (one oapl_loss_fwd_bwd call: log-prob
+scoring, per-rollout sums, group value estimate, loss, backward to dH and dW)
+over one synthetic batch of the Qwen-7B-shaped configuration (d = 4096,
+V = 151936, 8 prompts x 8 rollouts, truncated-lognormal lengths).  Inputs are
+resident in HBM before the timed region starts.
+
+Prints one JSON line: rollout tokens/s, the roofline figures of the dominant
+kernel (timed with HIP events on its own stream, inside the library), and the
+CPU oracle timed on a bounded sample of the same batch on this machine's host cores.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2516.6     # MI355X dense bf16 MFMA: 256 CU x 4096 flop/clk x 2.4 GHz
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="qwen7b", help="name in synth.CONFIGS")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample-tokens", type=int, default=384)
+    return ap.parse_args()
+
+
+def cpu_baseline(batch, n_tokens):
+    """The oracle as it stands, on the first rollouts of the batch cut to n_tokens in all."""
+    import numpy as np
+    import torch
+    from oracle import oapl_oracle as orc
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        threads = len(os.sched_getaffinity(0))
+    off = batch.seq_offsets.cpu().numpy()
+    lens = np.diff(off)
+    G = batch.cfg.n_rollouts
+    per = max(1, n_tokens // G)
+    take = np.minimum(lens[:G], per)                 # the first prompt's G rollouts, each cut to `per` tokens
+    rows = np.concatenate([np.arange(off[s], off[s] + take[s]) for s in range(G)])
+    f64 = lambda t: t.detach().cpu().to(torch.float64).numpy()
+    rows_t = torch.from_numpy(rows).to(batch.H.device)
+    H = f64(batch.H[rows_t])
+    W = f64(batch.W)
+    tok = batch.tokens[rows_t].cpu().numpy()
+    logq = f64(batch.logq[rows_t])
+    offs = np.concatenate([[0], np.cumsum(take)])
+    t0 = time.perf_counter()
+    orc.oapl_forward_backward(H, W, tok, logq, offs, f64(batch.rewards[:G]), np.zeros(G, dtype=np.int64), 1,
+                              batch.beta, backward=batch.cfg.backward)
+    dt = time.perf_counter() - t0
+    return {
+        "value": float(len(rows) / dt), "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
+        "sample": f"first prompt's {G} rollouts cut to {per} tokens each ({len(rows)} tokens), "
+                  f"fp64 numpy, forward{'+backward' if batch.cfg.backward else ''}, {dt:.1f} s",
+    }
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: the path is built and measured single-GPU only "
+              "(no collectives); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2602_19362_amd import oapl, synth
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU (there is no CPU fallback of the product path)", file=sys.stderr)
+        sys.exit(2)
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    cfg = synth.CONFIGS[args.workload]
+    batch = synth.make_batch(cfg, dev)
+    T, d, V = batch.T, cfg.d, cfg.V
+    dt_code = oapl.OAPL_BF16 if cfg.dtype == "bf16" else oapl.OAPL_F32
+    ws = torch.empty(oapl.workspace_bytes(T, d, V, batch.n_seq, batch.n_groups, dt_code, cfg.backward),
+                     dtype=torch.uint8, device=dev)
+    dH = torch.empty_like(batch.H) if cfg.backward else None
+    dW = torch.empty((V, d), dtype=torch.float32, device=dev) if cfg.backward else None
+
+    def step():
+        return oapl.loss_fwd_bwd(batch.H, batch.W, batch.tokens, batch.logq, batch.seq_offsets, batch.rewards,
+                                 batch.group_ids, batch.n_groups, batch.beta, backward=cfg.backward,
+                                 workspace=ws, dH=dH, dW=dW)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    oapl.timing_enable(True)
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        res = step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    kt = oapl.timing_read()
+    oapl.timing_enable(False)
+    status = oapl.read_device_status(ws)
+    loss = float(res.loss.item())
+    if status != 0 or loss != loss:
+        print(f"device status {status}, loss {loss}", file=sys.stderr)
+        sys.exit(1)
+
+    ms_per_step = 1e3 * elapsed / args.steps
+    tokens_per_s = T * args.steps / elapsed
+    flop_unit = 2.0 * V * d                                  # one V x d contraction per token
+    n_contractions = 3 if cfg.backward else 1                # logits, dH, dW (the recompute is not counted)
+    alg_tflops = tokens_per_s * flop_unit * n_contractions / 1e12
+    hw_tflops = tokens_per_s * flop_unit * (4 if cfg.backward else 1) / 1e12
+
+    # Each dense kernel executes 2*V*d flop per token it processes; over the
+    # timed steps every kernel sees every token once per step.
+    kernels = {}
+    for name, (ms, n) in kt.items():
+        if n == 0:
+            continue
+        tf = flop_unit * T * args.steps / (ms * 1e-3) / 1e12
+        kernels[name] = {"launches": n, "avg_ms": ms / n, "tflops": tf, "frac": tf / PEAK_BF16_TFLOPS}
+    dom = max(kernels, key=lambda k: kernels[k]["avg_ms"] * kernels[k]["launches"]) if kernels else None
+    roofline = None
+    if dom:
+        roofline = {"bound": "mfma", "kernel": dom, "achieved": kernels[dom]["tflops"], "peak": PEAK_BF16_TFLOPS,
+                    "unit": "TFLOP/s", "frac": kernels[dom]["frac"], "traffic": None,
+                    "avg_launch_ms": kernels[dom]["avg_ms"], "launches": kernels[dom]["launches"]}
+
+    out = {
+        "metric": "rollout tokens/s for OAPL logprob+loss fwd+bwd; % of bf16 MFMA peak",
+        "value": tokens_per_s, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": cfg.dtype, "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: d={d} V={V} {cfg.n_prompts} prompts x {cfg.n_rollouts} rollouts, "
+                               f"T={T} packed tokens, beta={cfg.beta}, {'fwd+bwd' if cfg.backward else 'fwd only'}"},
+        "algorithmic_tflops": alg_tflops, "frac_of_bf16_peak_algorithmic": alg_tflops / PEAK_BF16_TFLOPS,
+        "executed_tflops": hw_tflops, "frac_of_bf16_peak_executed": hw_tflops / PEAK_BF16_TFLOPS,
+        "kernels": kernels, "roofline": roofline, "loss": loss,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(batch, args.cpu_sample_tokens)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,192 @@
+/*
+ * oapl.h - C ABI of the OAPL trainer-step loss head for AMD MI355X (gfx950).
+ *
+ * The library scores sampled rollouts under the current policy pi and
+ * evaluates the OAPL objective on them ("LLMs Can Learn to Reason Via
+ * Off-Policy RL", Sec. 3.1), with its backward pass to the final hidden states
+ * and the LM-head weights.
+ *
+ * Notation (Sec. 3.1): x is a prompt, y_1..y_G the group of rollouts sampled
+ * for it from the lagged inference policy pi_vllm, r(x, y) the reward, beta
+ * the regularisation constant.
+ *
+ *   T         packed number of scored tokens over all rollouts
+ *   d, V      hidden size and vocabulary size
+ *   H [T, d]  final hidden states, row-major; row t predicts token y_t (the
+ *             caller has applied the next-token shift and dropped prompt and
+ *             padding positions)
+ *   W [V, d]  LM-head weights, row-major, no bias; logits z_t = W h_t
+ *
+ * General rules for every entry point
+ *   - Every pointer is DEVICE memory on the current HIP device unless the
+ *     comment says "host".  The caller owns all buffers; the library never
+ *     allocates, frees or keeps a pointer after the call returns.
+ *   - All work is enqueued on `stream` (a hipStream_t passed as void*, NULL =
+ *     the default stream).  No entry point synchronises with the host except
+ *     oapl_read_device_status.
+ *   - Inputs are never modified; outputs are fully overwritten.
+ *   - `workspace` must hold at least oapl_workspace_bytes(...) bytes for the
+ *     same sizes, aligned to 256 bytes.  Its contents are scratch.  Two calls
+ *     may run concurrently only with distinct workspaces.
+ *   - The return value is an oapl_status.  Errors the host can see (null
+ *     pointers, bad sizes, bad beta, short workspace) return before anything
+ *     is launched.  Errors in device data (token id outside [0, V), group id
+ *     outside [0, n_groups), empty group, offsets not starting at 0 / not
+ *     ending at T / decreasing) cannot be seen without a sync: the kernels
+ *     record the first such status in the workspace, never read or write out
+ *     of bounds because of it, and write NaN to the affected outputs (the
+ *     log-prob of a bad token; the loss for bad offsets or groups).
+ *     oapl_read_device_status fetches the record.
+ */
+#ifndef OAPL_H
+#define OAPL_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  OAPL_OK = 0,
+  OAPL_ERR_NULL = 1,        /* a required pointer is NULL */
+  OAPL_ERR_SHAPE = 2,       /* a size is non-positive or unsupported */
+  OAPL_ERR_DTYPE = 3,       /* dtype is not an oapl_dtype */
+  OAPL_ERR_OFFSETS = 4,     /* device: seq_offsets malformed */
+  OAPL_ERR_GROUP = 5,       /* device: group id out of range or empty group */
+  OAPL_ERR_BETA = 6,        /* beta (or loss_scale) not finite or beta <= 0 */
+  OAPL_ERR_WORKSPACE = 7,   /* workspace NULL, misaligned or too small */
+  OAPL_ERR_HIP = 8,         /* a HIP launch or runtime call failed */
+  OAPL_ERR_TOKEN_RANGE = 9  /* device: sampled token outside [0, V) */
+} oapl_status;
+
+typedef enum {
+  OAPL_F32 = 0,  /* H, W, dH are float; plain fp32 FMA arithmetic */
+  OAPL_BF16 = 1  /* H, W, dH are bfloat16 (raw uint16 bit patterns); MFMA with fp32 accumulation */
+} oapl_dtype;
+
+/* Human-readable name of a status (host pointer to a static string). */
+const char* oapl_status_string(int32_t status);
+
+/*
+ * Shape limits: T >= 0 (T == 0 is legal and yields loss = sum of squared
+ * advantages), 1 <= d, 1 <= V, d and V < 2^31, 0 <= n_seq, 1 <= n_groups.
+ * OAPL_BF16 additionally needs d to be a multiple of 8 (16-byte rows).
+ */
+
+/* Bytes of workspace the two calls below need for these sizes (host call, no
+ * GPU work).  with_backward = 0 sizes it for oapl_logprob_fwd and for
+ * oapl_loss_fwd_bwd with dH = dW = NULL.  Returns 0 for invalid sizes. */
+size_t oapl_workspace_bytes(int64_t T, int32_t d, int32_t V, int32_t n_seq,
+                            int32_t n_groups, int32_t dtype, int32_t with_backward);
+
+/*
+ * Per-token log-probability of the sampled token under pi (the ln pi(y_t | x,
+ * y_<t) whose sum over a rollout is the ln pi(y_i | x) of Eq. 3; soft-max over
+ * the full vocabulary at temperature 1, as the appendix's generation settings
+ * imply):
+ *
+ *     lse_t      = ln sum_v exp(z_{t,v}),   z_{t,v} = sum_k H[t,k] W[v,k]
+ *     logprob[t] = z_{t, tokens[t]} - lse_t          (<= 0)
+ *
+ * The T x V logits are produced tile by tile and reduced on the fly; they are
+ * never stored.
+ *
+ *   tokens      [T] int32, each in [0, V)
+ *   logprob_out [T] float
+ *   lse_out     [T] float, or NULL if not wanted
+ */
+int32_t oapl_logprob_fwd(const void* H, const void* W, const int32_t* tokens,
+                         int64_t T, int32_t d, int32_t V, int32_t dtype,
+                         float* logprob_out, float* lse_out,
+                         void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * OAPL objective and gradients on one packed batch (Sec. 3.1).
+ *
+ *   Delta_s = sum_{t in rollout s} (logprob[t] - logq[t])     ln pi(y|x)/pi_vllm(y|x), no length normalisation
+ *   V*_g    = beta ln( (1/G_g) sum_{s in group g} exp(r_s / beta) )                    Eq. 2
+ *   delta_s = beta Delta_s - (r_s - V*_{g(s)})
+ *   loss    = loss_scale * sum_s delta_s^2                                             Eq. 3
+ *   dH, dW  = d loss / d H, d loss / d W; V* and logq are constants (V* depends
+ *             on rewards only), so with c_t = loss_scale * 2 beta delta_{s(t)}
+ *             and p_t = softmax(z_t):
+ *               dH[t,:] = c_t (W[y_t,:] - sum_v p_{t,v} W[v,:])
+ *               dW[v,:] = sum_t c_t (1[v = y_t] - p_{t,v}) H[t,:]
+ *
+ * The same beta is used in Eq. 2 and Eq. 3, as the method section writes
+ * them.  loss_scale = 1 gives the paper's plain sum; it exists so a caller can
+ * average over a batch.
+ *
+ *   logq         [T] float, inference-policy log-probs of the same tokens
+ *   seq_offsets  [n_seq + 1] int64; rollout s owns tokens [off[s], off[s+1]);
+ *                off[0] = 0, off[n_seq] = T, non-decreasing (empty rollouts legal)
+ *   rewards      [n_seq] float (the paper's are binary; any finite value works)
+ *   group_ids    [n_seq] int32 in [0, n_groups), any order; G_g is the number
+ *                of rollouts carrying id g and must be >= 1 for every g
+ *   loss_out         [1] float
+ *   logprob_out      [T] float or NULL
+ *   seq_logratio_out [n_seq] float or NULL   (Delta_s)
+ *   vstar_out        [n_groups] float or NULL
+ *   dH  [T, d] in `dtype`, dW [V, d] float (overwritten, not accumulated);
+ *       pass both NULL to get the loss only.
+ */
+int32_t oapl_loss_fwd_bwd(const void* H, const void* W, const int32_t* tokens,
+                          const float* logq, const int64_t* seq_offsets,
+                          const float* rewards, const int32_t* group_ids,
+                          int64_t T, int32_t d, int32_t V, int32_t n_seq, int32_t n_groups,
+                          int32_t dtype, float beta, float loss_scale,
+                          float* loss_out, float* logprob_out, float* seq_logratio_out,
+                          float* vstar_out, void* dH, float* dW,
+                          void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Same as oapl_loss_fwd_bwd with separate constants, as the experimental
+ * section (Sec. 5) uses: beta_value in Eq. 2 and beta_loss in Eq. 3.
+ */
+int32_t oapl_loss_fwd_bwd_two_beta(const void* H, const void* W, const int32_t* tokens,
+                                   const float* logq, const int64_t* seq_offsets,
+                                   const float* rewards, const int32_t* group_ids,
+                                   int64_t T, int32_t d, int32_t V, int32_t n_seq, int32_t n_groups,
+                                   int32_t dtype, float beta_value, float beta_loss, float loss_scale,
+                                   float* loss_out, float* logprob_out, float* seq_logratio_out,
+                                   float* vstar_out, void* dH, float* dW,
+                                   void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Per-rollout sums over a packed stream (the reduction behind Delta_s in
+ * Eq. 3), exposed on its own: out[s] = sum_{t in [off[s], off[s+1])} x[t],
+ * accumulated in double in a fixed order (bit-reproducible).
+ *   x [off[n_seq]] float, seq_offsets [n_seq + 1] int64 (must be non-decreasing),
+ *   out [n_seq] double.  Needs no workspace.
+ */
+int32_t oapl_segmented_sum_f32(const float* x, const int64_t* seq_offsets, int32_t n_seq,
+                               double* out, void* stream);
+
+/*
+ * Waits for `stream`, then copies the device-side status recorded in
+ * `workspace` by the last call that used it into *status_out (host pointer).
+ */
+int32_t oapl_read_device_status(const void* workspace, void* stream, int32_t* status_out);
+
+/*
+ * Measurement aid, not part of the method.  The path's time is spent in four
+ * dense bf16 kernels: 0 = LM-head contraction fused with the streaming
+ * log-sum-exp (forward), 1 = soft-max recompute producing the logit gradient,
+ * 2 = the dH contraction, 3 = the dW contraction.  After
+ * oapl_timing_enable(1), every launch of these kernels is bracketed by a pair
+ * of HIP events recorded on the launch stream; oapl_timing_read waits for the
+ * recorded events of one kernel and returns the summed duration (milliseconds)
+ * and the number of launches since the last enable call (host pointers).
+ * oapl_timing_enable(0) switches recording off and drops the records.  Calls
+ * made while recording must not overlap on different host threads' streams if
+ * per-kernel attribution matters; the events themselves are stream-ordered.
+ */
+int32_t oapl_timing_enable(int32_t enable);
+int32_t oapl_timing_read(int32_t kernel, double* total_ms, int64_t* launches);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* OAPL_H */

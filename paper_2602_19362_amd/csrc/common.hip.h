@@ -1,0 +1,57 @@
+// Shared device-side definitions for the OAPL loss-head kernels (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace oapl {
+
+typedef __bf16 bf16_t;
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+typedef __attribute__((address_space(3))) void* lds_void_ptr;
+
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr double kLn2 = 0.6931471805599453094;
+// "minus infinity" that survives (m - m) without producing NaN.
+constexpr float kNegHuge = -3.0e38f;
+
+// Status words recorded by kernels; the values are those of oapl_status.
+constexpr int kErrOffsets = 4;
+constexpr int kErrGroup = 5;
+constexpr int kErrTokenRange = 9;
+
+// First device-side error wins; later ones are dropped.
+__device__ __forceinline__ void record_error(int* flag, int code) {
+  atomicCAS(flag, 0, code);
+}
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_down(v, o, 64);
+  return v;
+}
+
+__device__ __forceinline__ double wave_sum(double v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_down(v, o, 64);
+  return v;
+}
+
+// Workgroup ids are handed to the 8 XCDs round-robin, and each XCD has its own
+// L2.  This turns the hardware id into a logical id such that every XCD works
+// through one contiguous range of logical ids, so neighbouring tiles (which
+// share operand panels) meet in the same L2.  `total` need not be a multiple
+// of 8: launch round_up(total, 8) workgroups and drop ids >= total.
+__device__ __forceinline__ int xcd_logical_id(int bid, int total) {
+  const int per = (total + 7) >> 3;
+  return (bid & 7) * per + (bid >> 3);
+}
+
+}  // namespace oapl

@@ -1,0 +1,439 @@
+// C ABI of the OAPL loss head: argument checks, workspace plan, launch order.
+// Every step of the path runs in the kernels of this directory; nothing here
+// computes on the host and nothing falls back to a CPU path.
+#include "oapl.h"
+
+#include <math.h>
+#include <mutex>
+#include <utility>
+#include <vector>
+
+#include "gemm_bf16.hip.h"
+#include "gemm_f32.hip.h"
+#include "small_kernels.hip.h"
+
+namespace oapl {
+
+// 256 x 256 x 64 tiles, 4 wavefronts in a 2 x 2 grid, each a 128 x 128 patch
+// (4 x 4 MFMA blocks): 256 accumulator registers per lane, one wavefront per
+// SIMD, 128 KB of LDS for the two operand stages.
+typedef TileCfg<2, 2, 4, 4> Cfg;
+
+constexpr int64_t kPanelBf16 = 16384;  // token rows per backward panel (bf16 path)
+constexpr int64_t kPanelF32 = 4096;    // ... (fp32 path)
+constexpr int kStatusWords = 64;       // 256-byte header
+
+static inline int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
+
+struct Plan {
+  int64_t T = 0;
+  int d = 0, V = 0, n_seq = 0, n_groups = 0, dtype = 0;
+  bool bwd = false;
+  int n_parts = 0;     // soft-max partials per token
+  int64_t Tp = 0;      // rows of one backward panel
+  int64_t Vp = 0;      // row pitch of the dZ panel
+  size_t off_status = 0, off_partials = 0, off_zy = 0, off_lse2 = 0, off_diff = 0, off_coef = 0, off_delta = 0,
+         off_cseq = 0, off_vstar = 0, off_omp = 0, off_inv = 0, off_WT = 0, off_HT = 0, off_dZ = 0, off_dZT = 0, total = 0;
+};
+
+static bool make_plan(Plan& p, int64_t T, int d, int V, int n_seq, int n_groups, int dtype, bool bwd) {
+  if (T < 0 || d < 1 || V < 1 || n_seq < 0 || n_groups < 1) return false;
+  if (dtype != OAPL_F32 && dtype != OAPL_BF16) return false;
+  if (dtype == OAPL_BF16 && (d % 8) != 0) return false;
+  if ((int64_t)d > (1 << 22) || (int64_t)V > (1ll << 30)) return false;
+  p.T = T; p.d = d; p.V = V; p.n_seq = n_seq; p.n_groups = n_groups; p.dtype = dtype; p.bwd = bwd;
+  if (dtype == OAPL_BF16) {
+    const int64_t n_tiles = (T + Cfg::BN - 1) / Cfg::BN;
+    const int MT = (V + Cfg::BM - 1) / Cfg::BM;
+    int64_t splits = n_tiles > 0 ? (4096 + n_tiles - 1) / n_tiles : 1;
+    const int64_t max_splits = MT / 8 > 1 ? MT / 8 : 1;  // at least ~8 vocabulary tiles per workgroup
+    if (splits > max_splits) splits = max_splits;
+    if (splits > 64) splits = 64;
+    if (splits < 1) splits = 1;
+    p.n_parts = (int)splits;
+    p.Tp = T < kPanelBf16 ? round_up(T > 0 ? T : 1, Cfg::BN) : kPanelBf16;
+    p.Vp = round_up(V, 8);
+  } else {
+    p.n_parts = (V + 63) / 64;
+    p.Tp = T < kPanelF32 ? (T > 0 ? T : 1) : kPanelF32;
+    p.Vp = V;
+  }
+  size_t o = 0;
+  auto take = [&](size_t bytes) { size_t at = o; o += (bytes + 255) / 256 * 256; return at; };
+  const size_t Tn = (size_t)(T > 0 ? T : 1);
+  p.off_status = take(kStatusWords * 4);
+  p.off_partials = take(Tn * (size_t)p.n_parts * 8);
+  p.off_zy = take(Tn * 4);
+  p.off_lse2 = take(Tn * 4);
+  p.off_diff = take(Tn * 8);
+  p.off_coef = take(Tn * 4);
+  p.off_omp = take(Tn * 4);
+  p.off_inv = take(Tn * 4);
+  p.off_delta = take((size_t)(n_seq > 0 ? n_seq : 1) * 8);
+  p.off_cseq = take((size_t)(n_seq > 0 ? n_seq : 1) * 4);
+  p.off_vstar = take((size_t)n_groups * 8);
+  if (bwd) {
+    if (dtype == OAPL_BF16) {
+      p.off_WT = take((size_t)d * p.Vp * 2);
+      p.off_HT = take((size_t)d * p.Tp * 2);
+      p.off_dZ = take((size_t)p.Tp * p.Vp * 2);
+      p.off_dZT = take((size_t)V * p.Tp * 2);
+    } else {
+      p.off_dZ = take((size_t)p.Tp * p.Vp * 4);
+    }
+  }
+  p.total = o;
+  return true;
+}
+
+static inline unsigned grid1d(int64_t n, int per) { return (unsigned)((n + per - 1) / per); }
+
+// Optional per-kernel timing of the four dense kernels: when switched on, every
+// launch is bracketed by a pair of events recorded on the launch stream itself.
+enum DenseKernel { kFwdLse = 0, kBwdDz = 1, kBwdDh = 2, kBwdDw = 3, kNumDense = 4 };
+struct TimingState {
+  std::mutex mu;
+  bool on = false;
+  std::vector<std::pair<hipEvent_t, hipEvent_t>> ev[kNumDense];
+};
+static TimingState& timing() {
+  static TimingState t;
+  return t;
+}
+struct ScopedKernelTimer {
+  hipStream_t st;
+  hipEvent_t stop = nullptr;
+  ScopedKernelTimer(int which, hipStream_t s) : st(s) {
+    TimingState& t = timing();
+    std::lock_guard<std::mutex> g(t.mu);
+    if (!t.on) return;
+    hipEvent_t a, b;
+    if (hipEventCreate(&a) != hipSuccess) return;
+    if (hipEventCreate(&b) != hipSuccess) { (void)hipEventDestroy(a); return; }
+    (void)hipEventRecord(a, st);
+    stop = b;
+    t.ev[which].emplace_back(a, b);
+  }
+  ~ScopedKernelTimer() {
+    if (stop) (void)hipEventRecord(stop, st);
+  }
+};
+
+#define OAPL_LAUNCH_CHECK()                                   \
+  do {                                                        \
+    if (hipGetLastError() != hipSuccess) return OAPL_ERR_HIP; \
+  } while (0)
+
+template <class K>
+static bool allow_big_lds(K kernel, int bytes) {
+  return hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes) == hipSuccess;
+}
+
+static bool prepare_kernels() {
+  static std::once_flag once;
+  static bool ok = false;
+  std::call_once(once, [] {
+    ok = allow_big_lds(k_fwd_lse<Cfg>, Cfg::LDS_BYTES) && allow_big_lds(k_bwd_dz<Cfg>, Cfg::LDS_BYTES) &&
+         allow_big_lds(k_bwd_dh<Cfg>, Cfg::LDS_BYTES) && allow_big_lds(k_bwd_dw<Cfg>, Cfg::LDS_BYTES);
+  });
+  return ok;
+}
+
+// Steps a1-a3 of the path: partial soft-max statistics, sampled-token logit,
+// finish.  Writes logprob / lse if wanted, and (for the loss) lse in the
+// kernels' exponent domain plus logprob - logq in double.
+static int forward_scores(const Plan& p, const void* H, const void* W, const int32_t* tokens, const float* logq,
+                          float* logprob_out, float* lse_out, char* ws, bool keep_for_loss, hipStream_t st) {
+  int* status = (int*)(ws + p.off_status);
+  float2* partials = (float2*)(ws + p.off_partials);
+  float* zy = (float*)(ws + p.off_zy);
+  float* lse2 = keep_for_loss ? (float*)(ws + p.off_lse2) : nullptr;
+  double* diff = keep_for_loss ? (double*)(ws + p.off_diff) : nullptr;
+  float* omp = keep_for_loss ? (float*)(ws + p.off_omp) : nullptr;
+  float* inv = keep_for_loss ? (float*)(ws + p.off_inv) : nullptr;
+  const int64_t T = p.T;
+
+  k_fill_i32<<<1, 64, 0, st>>>(status, kStatusWords, 0);
+  OAPL_LAUNCH_CHECK();
+  if (T == 0) return OAPL_OK;
+
+  if (p.dtype == OAPL_BF16) {
+    if (!prepare_kernels()) return OAPL_ERR_HIP;
+    k_gather_logit<bf16_t, float><<<grid1d(T, 4), 256, 0, st>>>((const bf16_t*)H, (const bf16_t*)W, tokens, T, p.d,
+                                                                p.V, zy, status);
+    OAPL_LAUNCH_CHECK();
+    const int64_t n_tiles = (T + Cfg::BN - 1) / Cfg::BN;
+    const int64_t total = n_tiles * p.n_parts;
+    {
+      ScopedKernelTimer tm(kFwdLse, st);
+      k_fwd_lse<Cfg><<<(unsigned)round_up(total, 8), Cfg::NT, Cfg::LDS_BYTES, st>>>(
+          (const bf16_t*)W, (const bf16_t*)H, p.V, T, p.d, p.n_parts, partials);
+    }
+    OAPL_LAUNCH_CHECK();
+    k_lse_finish<true><<<grid1d(T, 256), 256, 0, st>>>(partials, p.n_parts, T, zy, logq, logprob_out, lse_out, lse2,
+                                                       diff, omp, inv);
+    OAPL_LAUNCH_CHECK();
+  } else {
+    k_gather_logit<float, double><<<grid1d(T, 4), 256, 0, st>>>((const float*)H, (const float*)W, tokens, T, p.d, p.V,
+                                                                zy, status);
+    OAPL_LAUNCH_CHECK();
+    F32Operand A{(const float*)H, p.d, 1}, B{(const float*)W, p.d, 1};
+    dim3 grid(grid1d(p.V, 64), grid1d(T, 64));
+    k_gemm_f32<<<grid, 256, 0, st>>>(A, B, T, (int64_t)p.V, (int64_t)p.d, EpiLseF32{partials, T});
+    OAPL_LAUNCH_CHECK();
+    k_lse_finish<false><<<grid1d(T, 256), 256, 0, st>>>(partials, p.n_parts, T, zy, logq, logprob_out, lse_out, lse2,
+                                                        diff, omp, inv);
+    OAPL_LAUNCH_CHECK();
+  }
+  return OAPL_OK;
+}
+
+// Steps a8-a10: panel by panel, recompute the soft-max tiles into dZ and run
+// the two gradient contractions.
+static int backward_grads(const Plan& p, const void* H, const void* W, const int32_t* tokens, void* dH, float* dW,
+                          char* ws, hipStream_t st) {
+  const int64_t T = p.T;
+  const int d = p.d, V = p.V;
+  const float* lse2 = (const float*)(ws + p.off_lse2);
+  const float* coef = (const float*)(ws + p.off_coef);  // bf16: f_t = c_t (1 - p_y); fp32: c_t
+  const float* inv = (const float*)(ws + p.off_inv);
+  if (T == 0) {
+    k_fill_f32<<<1024, 256, 0, st>>>(dW, (int64_t)V * d, 0.f);
+    OAPL_LAUNCH_CHECK();
+    return OAPL_OK;
+  }
+  if (p.dtype == OAPL_BF16) {
+    bf16_t* WT = (bf16_t*)(ws + p.off_WT);
+    bf16_t* HT = (bf16_t*)(ws + p.off_HT);
+    bf16_t* dZ = (bf16_t*)(ws + p.off_dZ);
+    bf16_t* dZT = (bf16_t*)(ws + p.off_dZT);
+    {
+      dim3 grid(grid1d(p.Vp, 64), grid1d(d, 64));
+      k_transpose_bf16<<<grid, 256, 0, st>>>((const bf16_t*)W, V, d, d, nullptr, WT, p.Vp, p.Vp);
+      OAPL_LAUNCH_CHECK();
+    }
+    const int MTv = (V + Cfg::BM - 1) / Cfg::BM, MTd = (d + Cfg::BM - 1) / Cfg::BM;
+    for (int64_t t0 = 0; t0 < T; t0 += p.Tp) {
+      const int64_t nv = (T - t0) < p.Tp ? (T - t0) : p.Tp;
+      const int64_t Kt = round_up(nv, Cfg::BN);
+      const bf16_t* Hp = (const bf16_t*)H + t0 * d;
+      const int64_t NTl = (nv + Cfg::BN - 1) / Cfg::BN;
+      {
+        dim3 grid(grid1d(Kt, 64), grid1d(d, 64));
+        k_transpose_bf16<<<grid, 256, 0, st>>>(Hp, nv, d, d, coef + t0, HT, p.Tp, Kt);
+        OAPL_LAUNCH_CHECK();
+      }
+      {
+        ScopedKernelTimer tm(kBwdDz, st);
+        k_bwd_dz<Cfg><<<(unsigned)round_up(MTv * NTl, 8), Cfg::NT, Cfg::LDS_BYTES, st>>>(
+            (const bf16_t*)W, Hp, V, nv, d, tokens + t0, lse2 + t0, inv + t0, dZ, p.Vp, dZT, p.Tp);
+      }
+      OAPL_LAUNCH_CHECK();
+      {
+        ScopedKernelTimer tm(kBwdDh, st);
+        k_bwd_dh<Cfg><<<(unsigned)round_up(MTd * NTl, 8), Cfg::NT, Cfg::LDS_BYTES, st>>>(
+            WT, dZ, d, nv, V, p.Vp, coef + t0, (bf16_t*)dH + t0 * d);
+      }
+      OAPL_LAUNCH_CHECK();
+      {
+        ScopedKernelTimer tm(kBwdDw, st);
+        k_bwd_dw<Cfg><<<(unsigned)round_up((int64_t)MTd * MTv, 8), Cfg::NT, Cfg::LDS_BYTES, st>>>(
+            HT, dZT, d, V, p.Tp, (int)Kt, dW, t0 > 0 ? 1 : 0);
+      }
+      OAPL_LAUNCH_CHECK();
+    }
+  } else {
+    float* dZ = (float*)(ws + p.off_dZ);
+    for (int64_t t0 = 0; t0 < T; t0 += p.Tp) {
+      const int64_t nv = (T - t0) < p.Tp ? (T - t0) : p.Tp;
+      const float* Hp = (const float*)H + t0 * d;
+      {
+        F32Operand A{Hp, d, 1}, B{(const float*)W, d, 1};
+        dim3 grid(grid1d(V, 64), grid1d(nv, 64));
+        k_gemm_f32<<<grid, 256, 0, st>>>(A, B, nv, (int64_t)V, (int64_t)d,
+                                         EpiDzF32{tokens + t0, lse2 + t0, coef + t0, dZ, (int64_t)V});
+        OAPL_LAUNCH_CHECK();
+      }
+      {  // dH[t][j] = sum_v dZ[t][v] W[v][j]
+        F32Operand A{dZ, V, 1}, B{(const float*)W, 1, d};
+        dim3 grid(grid1d(d, 64), grid1d(nv, 64));
+        k_gemm_f32<<<grid, 256, 0, st>>>(A, B, nv, (int64_t)d, (int64_t)V, EpiStoreF32{(float*)dH + t0 * d, d, 0});
+        OAPL_LAUNCH_CHECK();
+      }
+      {  // dW[v][j] (+)= sum_t dZ[t][v] H[t][j]
+        F32Operand A{dZ, 1, V}, B{Hp, 1, d};
+        dim3 grid(grid1d(d, 64), grid1d(V, 64));
+        k_gemm_f32<<<grid, 256, 0, st>>>(A, B, (int64_t)V, (int64_t)d, nv, EpiStoreF32{dW, d, t0 > 0 ? 1 : 0});
+        OAPL_LAUNCH_CHECK();
+      }
+    }
+  }
+  return OAPL_OK;
+}
+
+static int check_workspace(const void* ws, size_t have, size_t need) {
+  if (ws == nullptr || ((uintptr_t)ws & 255) != 0 || have < need) return OAPL_ERR_WORKSPACE;
+  return OAPL_OK;
+}
+
+static int loss_impl(const void* H, const void* W, const int32_t* tokens, const float* logq,
+                     const int64_t* seq_offsets, const float* rewards, const int32_t* group_ids, int64_t T, int32_t d,
+                     int32_t V, int32_t n_seq, int32_t n_groups, int32_t dtype, float beta_value, float beta_loss,
+                     float loss_scale, float* loss_out, float* logprob_out, float* seq_logratio_out, float* vstar_out,
+                     void* dH, float* dW, void* workspace, size_t workspace_bytes, void* stream) {
+  if (dtype != OAPL_F32 && dtype != OAPL_BF16) return OAPL_ERR_DTYPE;
+  const bool bwd = (dH != nullptr) || (dW != nullptr);
+  Plan p;
+  if (!make_plan(p, T, d, V, n_seq, n_groups, dtype, bwd)) return OAPL_ERR_SHAPE;
+  // gradients come as a pair; an empty batch has no dH rows, so its pointer may be NULL
+  if (!W || !seq_offsets || !loss_out || (bwd && (!dW || (T > 0 && !dH)))) return OAPL_ERR_NULL;
+  if (T > 0 && (!H || !tokens || !logq)) return OAPL_ERR_NULL;
+  if (n_seq > 0 && (!rewards || !group_ids)) return OAPL_ERR_NULL;
+  if (!(beta_value > 0.f) || !(beta_loss > 0.f) || !isfinite(beta_value) || !isfinite(beta_loss) ||
+      !isfinite(loss_scale))
+    return OAPL_ERR_BETA;
+  if (int rc = check_workspace(workspace, workspace_bytes, p.total)) return rc;
+
+  hipStream_t st = (hipStream_t)stream;
+  char* ws = (char*)workspace;
+  if (int rc = forward_scores(p, H, W, tokens, logq, logprob_out, nullptr, ws, true, st)) return rc;
+
+  double* Delta = (double*)(ws + p.off_delta);
+  float* cseq = (float*)(ws + p.off_cseq);
+  if (n_seq > 0) {
+    k_segmented_sum<double><<<n_seq, 256, 0, st>>>((const double*)(ws + p.off_diff), seq_offsets, n_seq, T, Delta);
+    OAPL_LAUNCH_CHECK();
+  }
+  k_group_value_loss<<<1, 256, 0, st>>>(Delta, rewards, group_ids, seq_offsets, n_seq, n_groups, T,
+                                        (double)beta_value, (double)beta_loss, (double)loss_scale,
+                                        (double*)(ws + p.off_vstar), cseq, loss_out, seq_logratio_out, vstar_out,
+                                        (int*)(ws + p.off_status));
+  OAPL_LAUNCH_CHECK();
+  if (!bwd) return OAPL_OK;
+
+  if (T > 0) {
+    float* coef = (float*)(ws + p.off_coef);
+    k_fill_f32<<<grid1d(T, 256 * 8), 256, 0, st>>>(coef, T, 0.f);
+    OAPL_LAUNCH_CHECK();
+    if (n_seq > 0) {
+      const float* factor = p.dtype == OAPL_BF16 ? (const float*)(ws + p.off_omp) : nullptr;
+      k_token_coefficients<<<n_seq, 256, 0, st>>>(cseq, seq_offsets, n_seq, T, factor, coef);
+      OAPL_LAUNCH_CHECK();
+    }
+  }
+  return backward_grads(p, H, W, tokens, dH, dW, ws, st);
+}
+
+}  // namespace oapl
+
+using namespace oapl;
+
+extern "C" {
+
+const char* oapl_status_string(int32_t status) {
+  switch (status) {
+    case OAPL_OK: return "ok";
+    case OAPL_ERR_NULL: return "a required pointer is NULL";
+    case OAPL_ERR_SHAPE: return "a size is non-positive or unsupported";
+    case OAPL_ERR_DTYPE: return "unknown dtype";
+    case OAPL_ERR_OFFSETS: return "seq_offsets malformed";
+    case OAPL_ERR_GROUP: return "group id out of range or empty group";
+    case OAPL_ERR_BETA: return "beta must be positive and finite (loss_scale finite)";
+    case OAPL_ERR_WORKSPACE: return "workspace NULL, misaligned or too small";
+    case OAPL_ERR_HIP: return "HIP launch or runtime call failed";
+    case OAPL_ERR_TOKEN_RANGE: return "sampled token outside [0, V)";
+    default: return "unknown status";
+  }
+}
+
+size_t oapl_workspace_bytes(int64_t T, int32_t d, int32_t V, int32_t n_seq, int32_t n_groups, int32_t dtype,
+                            int32_t with_backward) {
+  Plan p;
+  if (!make_plan(p, T, d, V, n_seq, n_groups, dtype, with_backward != 0)) return 0;
+  return p.total;
+}
+
+int32_t oapl_logprob_fwd(const void* H, const void* W, const int32_t* tokens, int64_t T, int32_t d, int32_t V,
+                         int32_t dtype, float* logprob_out, float* lse_out, void* workspace, size_t workspace_bytes,
+                         void* stream) {
+  if (dtype != OAPL_F32 && dtype != OAPL_BF16) return OAPL_ERR_DTYPE;
+  Plan p;
+  if (!make_plan(p, T, d, V, 0, 1, dtype, false)) return OAPL_ERR_SHAPE;
+  if (!W) return OAPL_ERR_NULL;
+  if (T > 0 && (!H || !tokens || !logprob_out)) return OAPL_ERR_NULL;
+  if (int rc = check_workspace(workspace, workspace_bytes, p.total)) return rc;
+  return forward_scores(p, H, W, tokens, nullptr, logprob_out, lse_out, (char*)workspace, false, (hipStream_t)stream);
+}
+
+int32_t oapl_loss_fwd_bwd(const void* H, const void* W, const int32_t* tokens, const float* logq,
+                          const int64_t* seq_offsets, const float* rewards, const int32_t* group_ids, int64_t T,
+                          int32_t d, int32_t V, int32_t n_seq, int32_t n_groups, int32_t dtype, float beta,
+                          float loss_scale, float* loss_out, float* logprob_out, float* seq_logratio_out,
+                          float* vstar_out, void* dH, float* dW, void* workspace, size_t workspace_bytes,
+                          void* stream) {
+  return loss_impl(H, W, tokens, logq, seq_offsets, rewards, group_ids, T, d, V, n_seq, n_groups, dtype, beta, beta,
+                   loss_scale, loss_out, logprob_out, seq_logratio_out, vstar_out, dH, dW, workspace,
+                   workspace_bytes, stream);
+}
+
+int32_t oapl_loss_fwd_bwd_two_beta(const void* H, const void* W, const int32_t* tokens, const float* logq,
+                                   const int64_t* seq_offsets, const float* rewards, const int32_t* group_ids,
+                                   int64_t T, int32_t d, int32_t V, int32_t n_seq, int32_t n_groups, int32_t dtype,
+                                   float beta_value, float beta_loss, float loss_scale, float* loss_out,
+                                   float* logprob_out, float* seq_logratio_out, float* vstar_out, void* dH, float* dW,
+                                   void* workspace, size_t workspace_bytes, void* stream) {
+  return loss_impl(H, W, tokens, logq, seq_offsets, rewards, group_ids, T, d, V, n_seq, n_groups, dtype, beta_value,
+                   beta_loss, loss_scale, loss_out, logprob_out, seq_logratio_out, vstar_out, dH, dW, workspace,
+                   workspace_bytes, stream);
+}
+
+int32_t oapl_segmented_sum_f32(const float* x, const int64_t* seq_offsets, int32_t n_seq, double* out, void* stream) {
+  if (n_seq < 0) return OAPL_ERR_SHAPE;
+  if (n_seq == 0) return OAPL_OK;
+  if (!x || !seq_offsets || !out) return OAPL_ERR_NULL;
+  k_segmented_sum<float><<<n_seq, 256, 0, (hipStream_t)stream>>>(x, seq_offsets, n_seq, -1, out);
+  OAPL_LAUNCH_CHECK();
+  return OAPL_OK;
+}
+
+int32_t oapl_timing_enable(int32_t enable) {
+  TimingState& t = timing();
+  std::lock_guard<std::mutex> g(t.mu);
+  for (auto& v : t.ev) {
+    for (auto& e : v) {
+      (void)hipEventDestroy(e.first);
+      (void)hipEventDestroy(e.second);
+    }
+    v.clear();
+  }
+  t.on = enable != 0;
+  return OAPL_OK;
+}
+
+int32_t oapl_timing_read(int32_t kernel, double* total_ms, int64_t* launches) {
+  if (kernel < 0 || kernel >= kNumDense) return OAPL_ERR_SHAPE;
+  if (!total_ms || !launches) return OAPL_ERR_NULL;
+  TimingState& t = timing();
+  std::lock_guard<std::mutex> g(t.mu);
+  double sum = 0.0;
+  for (auto& e : t.ev[kernel]) {
+    if (hipEventSynchronize(e.second) != hipSuccess) return OAPL_ERR_HIP;
+    float ms = 0.f;
+    if (hipEventElapsedTime(&ms, e.first, e.second) != hipSuccess) return OAPL_ERR_HIP;
+    sum += ms;
+  }
+  *total_ms = sum;
+  *launches = (int64_t)t.ev[kernel].size();
+  return OAPL_OK;
+}
+
+int32_t oapl_read_device_status(const void* workspace, void* stream, int32_t* status_out) {
+  if (!workspace || !status_out) return OAPL_ERR_NULL;
+  if (hipStreamSynchronize((hipStream_t)stream) != hipSuccess) return OAPL_ERR_HIP;
+  int32_t v = 0;
+  if (hipMemcpy(&v, workspace, sizeof(v), hipMemcpyDeviceToHost) != hipSuccess) return OAPL_ERR_HIP;
+  *status_out = v;
+  return OAPL_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,226 @@
+// The O(T) and O(N) steps of the OAPL loss head: sampled-token logit gather,
+// log-sum-exp finish, per-rollout segmented sums, group value estimate and
+// loss (Sec. 3.1, Eq. 2 and Eq. 3), token coefficients, and the operand
+// transposes used by the backward GEMMs.  All bandwidth-trivial next to the
+// three V x d contractions; written for exactness and a fixed summation order.
+#pragma once
+
+#include "common.hip.h"
+
+namespace oapl {
+
+__device__ __forceinline__ float to_f32(float x) { return x; }
+__device__ __forceinline__ float to_f32(bf16_t x) { return (float)x; }
+
+__global__ void k_fill_i32(int32_t* p, int64_t n, int32_t v) {
+  for (int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) p[i] = v;
+}
+__global__ void k_fill_f32(float* p, int64_t n, float v) {
+  for (int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) p[i] = v;
+}
+
+// z_{t, y_t} = sum_k H[t][k] * W[y_t][k]: one wavefront per token, the gathered
+// W row is read with the index exactly as given (checked against [0, V)).
+// ACC is double for fp32 inputs and float for bf16 inputs (whose products are
+// exact in fp32).
+template <class T, class ACC>
+__global__ void __launch_bounds__(256)
+k_gather_logit(const T* __restrict__ H, const T* __restrict__ W, const int32_t* __restrict__ tokens,
+               int64_t Ttok, int d, int V, float* __restrict__ zy, int* __restrict__ err) {
+  const int lane = threadIdx.x & 63;
+  const int64_t t = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (t >= Ttok) return;
+  const int y = tokens[t];
+  if (y < 0 || y >= V) {
+    if (lane == 0) {
+      record_error(err, kErrTokenRange);
+      zy[t] = __builtin_nanf("");
+    }
+    return;
+  }
+  const T* h = H + t * d;
+  const T* w = W + (int64_t)y * d;
+  ACC acc = 0;
+  for (int k = lane; k < d; k += 64) acc += (ACC)to_f32(h[k]) * (ACC)to_f32(w[k]);
+  acc = wave_sum(acc);
+  if (lane == 0) zy[t] = (float)acc;
+}
+
+// Merges the per-split soft-max partials of each token and finishes
+//   lse_t = ln sum_v exp(z_tv),   logprob_t = min(z_{t,y_t} - lse_t, 0).
+// A partial is (m, s) with s = sum b^(zeta - m): LOG2 = true means zeta =
+// z * log2(e), b = 2 (the MFMA kernel's epilogue); false means zeta = z, b = e.
+// Everything after the fp32 partials is done in double.
+template <bool LOG2>
+__global__ void __launch_bounds__(256)
+k_lse_finish(const float2* __restrict__ partials, int n_parts, int64_t Ttok, const float* __restrict__ zy,
+             const float* __restrict__ logq, float* __restrict__ logprob_out, float* __restrict__ lse_out,
+             float* __restrict__ lse2_ws, double* __restrict__ diff_ws, float* __restrict__ omp_ws,
+             float* __restrict__ inv_omp_ws) {
+  const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (t >= Ttok) return;
+  float M = kNegHuge;
+  for (int p = 0; p < n_parts; ++p) M = fmaxf(M, partials[(int64_t)p * Ttok + t].x);
+  double S = 0.0;
+  for (int p = 0; p < n_parts; ++p) {
+    const float2 a = partials[(int64_t)p * Ttok + t];
+    const double e = (double)a.x - (double)M;
+    S += (double)a.y * (LOG2 ? exp2(e) : exp(e));
+  }
+  const double lse = LOG2 ? ((double)M + log2(S)) * kLn2 : (double)M + log(S);
+  double lp = (double)zy[t] - lse;   // NaN if the token was out of range
+  if (lp > 0.0) lp = 0.0;            // the gathered logit is rounded separately from the sum
+  if (logprob_out) logprob_out[t] = (float)lp;
+  if (lse_out) lse_out[t] = (float)lse;
+  // the backward kernels want lse in the domain their exponentials work in
+  if (lse2_ws) lse2_ws[t] = (float)(LOG2 ? lse * (double)1.4426950408889634074 : lse);
+  if (diff_ws) diff_ws[t] = lp - (double)logq[t];
+  // 1 - p_{t,y_t}, accurate also when the sampled token has almost all the mass;
+  // its reciprocal normalises the bf16 gradient rows (0 switches a row off when
+  // the soft-max is one-hot at y_t to working precision, or the token is bad)
+  if (omp_ws) {
+    const double omp = -expm1(lp);
+    const bool ok = omp > 1e-30;
+    omp_ws[t] = ok ? (float)omp : 0.f;
+    inv_omp_ws[t] = ok ? (float)(1.0 / omp) : 0.f;
+  }
+}
+
+// out[s] = sum_{t in [off[s], off[s+1])} x[t] in double: one workgroup per
+// rollout, each thread a strided partial in a fixed order, wavefront shuffle
+// reduction, then the 4 wave totals in order.  Bit-reproducible.  Offsets are
+// clamped to [0, limit] (limit < 0: only to a >= 0, b >= a) so malformed input
+// cannot read below the buffer or, with a limit, past it.
+template <class T>
+__global__ void __launch_bounds__(256)
+k_segmented_sum(const T* __restrict__ x, const int64_t* __restrict__ off, int n_seq, int64_t limit,
+                double* __restrict__ out) {
+  __shared__ double wsum[4];
+  const int s = blockIdx.x;
+  if (s >= n_seq) return;
+  int64_t a = off[s], b = off[s + 1];
+  a = a < 0 ? 0 : a;
+  b = b < a ? a : b;
+  if (limit >= 0) {
+    a = a > limit ? limit : a;
+    b = b > limit ? limit : b;
+  }
+  double acc = 0.0;
+  for (int64_t t = a + threadIdx.x; t < b; t += 256) acc += (double)x[t];
+  acc = wave_sum(acc);
+  if ((threadIdx.x & 63) == 0) wsum[threadIdx.x >> 6] = acc;
+  __syncthreads();
+  if (threadIdx.x == 0) out[s] = ((wsum[0] + wsum[1]) + wsum[2]) + wsum[3];
+}
+
+// Group value estimate, residuals and loss (one workgroup; N and P are small).
+//   V*_g    = beta_v ln( (1/G_g) sum_{s in g} exp(r_s / beta_v) )            Eq. 2
+//           = m_g + beta_v ln( (1/G_g) sum exp((r_s - m_g) / beta_v) ),  m_g = max_{s in g} r_s
+//             (same value; the shift keeps exp() in range for small beta and
+//             makes all-equal rewards return exactly r)
+//   delta_s = beta_l Delta_s - (r_s - V*_{g(s)})
+//   loss    = scale sum_s delta_s^2                                           Eq. 3
+//   cseq_s  = scale 2 beta_l delta_s      (d loss / d ln pi(y_t) for every token of s)
+// Also validates offsets and group ids; on a violation the loss is NaN and the
+// status word is set.
+__global__ void __launch_bounds__(256)
+k_group_value_loss(const double* __restrict__ Delta, const float* __restrict__ rewards,
+                   const int32_t* __restrict__ gid, const int64_t* __restrict__ off, int n_seq, int n_groups,
+                   int64_t Ttok, double beta_v, double beta_l, double scale, double* __restrict__ vstar_ws,
+                   float* __restrict__ cseq, float* __restrict__ loss_out, float* __restrict__ seq_logratio_out,
+                   float* __restrict__ vstar_out, int* __restrict__ err) {
+  __shared__ double wsum[4];
+  __shared__ int bad;
+  const int tid = threadIdx.x;
+  if (tid == 0) bad = 0;
+  __syncthreads();
+
+  if (tid == 0 && (off[0] != 0 || off[n_seq] != Ttok)) { bad = kErrOffsets; }
+  for (int s = tid; s < n_seq; s += 256) {
+    if (off[s + 1] < off[s]) atomicCAS(&bad, 0, kErrOffsets);
+    if (gid[s] < 0 || gid[s] >= n_groups) atomicCAS(&bad, 0, kErrGroup);
+  }
+  for (int g = tid; g < n_groups; g += 256) {
+    double m = -1.0e300;
+    int cnt = 0;
+    for (int s = 0; s < n_seq; ++s)
+      if (gid[s] == g) { m = fmax(m, (double)rewards[s]); ++cnt; }
+    double v = 0.0;
+    if (cnt == 0) {
+      atomicCAS(&bad, 0, kErrGroup);
+      v = __builtin_nan("");
+    } else {
+      double sum = 0.0;
+      for (int s = 0; s < n_seq; ++s)
+        if (gid[s] == g) sum += exp(((double)rewards[s] - m) / beta_v);
+      v = m + beta_v * log(sum / (double)cnt);
+    }
+    vstar_ws[g] = v;
+    if (vstar_out) vstar_out[g] = (float)v;
+  }
+  __threadfence_block();
+  __syncthreads();
+
+  double acc = 0.0;
+  for (int s = tid; s < n_seq; s += 256) {
+    const int g = gid[s];
+    const double v = (g >= 0 && g < n_groups) ? vstar_ws[g] : __builtin_nan("");
+    const double delta = beta_l * Delta[s] - ((double)rewards[s] - v);
+    cseq[s] = (float)(scale * 2.0 * beta_l * delta);
+    if (seq_logratio_out) seq_logratio_out[s] = (float)Delta[s];
+    acc += delta * delta;
+  }
+  acc = wave_sum(acc);
+  if ((tid & 63) == 0) wsum[tid >> 6] = acc;
+  __syncthreads();
+  if (tid == 0) {
+    double loss = scale * (((wsum[0] + wsum[1]) + wsum[2]) + wsum[3]);
+    if (bad) {
+      loss = __builtin_nan("");
+      record_error(err, bad);
+    }
+    loss_out[0] = (float)loss;
+  }
+}
+
+// coef[t] = cseq[s(t)] (times factor[t] if given): one workgroup per rollout
+// writes its token range (clamped to [0, T], so malformed offsets cannot write
+// out of bounds).
+__global__ void __launch_bounds__(256)
+k_token_coefficients(const float* __restrict__ cseq, const int64_t* __restrict__ off, int n_seq, int64_t Ttok,
+                     const float* __restrict__ factor, float* __restrict__ coef) {
+  const int s = blockIdx.x;
+  if (s >= n_seq) return;
+  int64_t a = off[s], b = off[s + 1];
+  a = a < 0 ? 0 : (a > Ttok ? Ttok : a);
+  b = b < a ? a : (b > Ttok ? Ttok : b);
+  const float c = cseq[s];
+  for (int64_t t = a + threadIdx.x; t < b; t += 256) coef[t] = factor ? c * factor[t] : c;
+}
+
+// dst[c][r] = src[r][c] * (row_scale ? row_scale[r] : 1) for r < rows, c < cols;
+// dst has `dst_ld` columns and columns in [rows, zero_to) are cleared.  64 x 64
+// tiles through LDS.  A scaled element is rounded to bf16 once (nearest even).
+__global__ void __launch_bounds__(256)
+k_transpose_bf16(const bf16_t* __restrict__ src, int64_t rows, int64_t cols, int64_t src_ld,
+                 const float* __restrict__ row_scale, bf16_t* __restrict__ dst, int64_t dst_ld, int64_t zero_to) {
+  __shared__ bf16_t tile[64][66];
+  const int64_t r0 = (int64_t)blockIdx.x * 64, c0 = (int64_t)blockIdx.y * 64;
+  const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+  for (int i = ty; i < 64; i += 4) {
+    const int64_t r = r0 + i, c = c0 + tx;
+    bf16_t v = (bf16_t)0.f;
+    if (r < rows && c < cols) {
+      v = src[r * src_ld + c];
+      if (row_scale) v = (bf16_t)((float)v * row_scale[r]);
+    }
+    tile[i][tx] = v;
+  }
+  __syncthreads();
+  for (int i = ty; i < 64; i += 4) {
+    const int64_t c = c0 + i, r = r0 + tx;
+    if (c < cols && r < zero_to) dst[c * dst_ld + r] = tile[tx][i];
+  }
+}
+
+}  // namespace oapl

@@ -1,0 +1,90 @@
+"""The C-ABI library: it loads, exports every declared symbol, and its host-side
+argument checks answer without a GPU (they return before any launch)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2602_19362_amd import oapl
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "oapl.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(oapl_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = _declared_symbols()
+    assert "oapl_logprob_fwd" in names and "oapl_loss_fwd_bwd" in names
+    handle = ctypes.CDLL(oapl.lib_path())
+    for n in names:
+        assert hasattr(handle, n), n
+    assert set(names) == set(oapl._SIGNATURES), "binding and header disagree"
+
+
+def test_status_strings():
+    L = oapl.lib()
+    assert L.oapl_status_string(0) == b"ok"
+    seen = {L.oapl_status_string(i) for i in range(10)}
+    assert len(seen) == 10 and L.oapl_status_string(77) == b"unknown status"
+
+
+def test_workspace_bytes_host_logic():
+    wb = oapl.workspace_bytes
+    small = wb(256, 64, 1024, 8, 2, oapl.OAPL_F32, False)
+    assert small > 0 and small % 256 == 0
+    assert wb(256, 64, 1024, 8, 2, oapl.OAPL_F32, True) > small
+    # the bf16 backward workspace is dominated by the two dZ panels, which stop growing at the panel size
+    a = wb(16384, 4096, 151936, 64, 8, oapl.OAPL_BF16, True)
+    b = wb(1 << 20, 4096, 151936, 64, 8, oapl.OAPL_BF16, True)
+    assert a > 2 * 16384 * 151936 * 2 and b - a < 64 * (1 << 20)
+    # invalid sizes
+    assert wb(-1, 64, 1024, 8, 2, 0, False) == 0
+    assert wb(256, 0, 1024, 8, 2, 0, False) == 0
+    assert wb(256, 64, 0, 8, 2, 0, False) == 0
+    assert wb(256, 64, 1024, 8, 0, 0, False) == 0
+    assert wb(256, 64, 1024, 8, 2, 5, False) == 0
+    assert wb(256, 60, 1024, 8, 2, oapl.OAPL_BF16, False) == 0     # bf16 rows must be 16-byte multiples
+    assert wb(0, 64, 1024, 0, 1, oapl.OAPL_BF16, True) > 0          # an empty batch is legal
+
+
+def test_host_side_errors_return_before_any_launch():
+    L = oapl.lib()
+    one = ctypes.c_void_p(256)          # never dereferenced: the checks below fail first
+    # dtype / shape / null
+    assert L.oapl_logprob_fwd(one, one, one, 4, 8, 8, 7, one, None, one, 1 << 20, None) == 3
+    assert L.oapl_logprob_fwd(one, one, one, 4, 0, 8, 0, one, None, one, 1 << 20, None) == 2
+    assert L.oapl_logprob_fwd(None, one, one, 4, 8, 8, 0, one, None, one, 1 << 20, None) == 1
+    # workspace: null, misaligned, too small
+    assert L.oapl_logprob_fwd(one, one, one, 4, 8, 8, 0, one, None, None, 1 << 20, None) == 7
+    assert L.oapl_logprob_fwd(one, one, one, 4, 8, 8, 0, one, None, ctypes.c_void_p(260), 1 << 20, None) == 7
+    assert L.oapl_logprob_fwd(one, one, one, 4, 8, 8, 0, one, None, one, 16, None) == 7
+
+    def loss(beta=1.0, scale=1.0, dH=one, dW=one, dtype=0, n_groups=1, ws_bytes=1 << 24):
+        return L.oapl_loss_fwd_bwd(one, one, one, one, one, one, one, 4, 8, 8, 2, n_groups, dtype,
+                                   beta, scale, one, None, None, None, dH, dW, one, ws_bytes, None)
+    assert loss(beta=0.0) == 6 and loss(beta=-1.0) == 6 and loss(beta=float("nan")) == 6
+    assert loss(beta=float("inf")) == 6 and loss(scale=float("inf")) == 6
+    assert loss(dH=None) == 1 and loss(dW=None) == 1          # gradients come as a pair
+    assert loss(dtype=9) == 3 and loss(n_groups=0) == 2 and loss(ws_bytes=64) == 7
+    assert L.oapl_loss_fwd_bwd_two_beta(one, one, one, one, one, one, one, 4, 8, 8, 2, 1, 0, 1.0, 0.0, 1.0,
+                                        one, None, None, None, one, one, one, 1 << 24, None) == 6
+    assert L.oapl_segmented_sum_f32(None, one, 3, one, None) == 1
+    assert L.oapl_segmented_sum_f32(one, one, -1, one, None) == 2
+    assert L.oapl_segmented_sum_f32(None, None, 0, None, None) == 0
+    assert L.oapl_read_device_status(None, None, None) == 1
+
+
+def test_product_path_has_no_cpu_fallback():
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("checked on the CPU-only box")
+    H = torch.zeros(4, 8)
+    W = torch.zeros(8, 8)
+    tok = torch.zeros(4, dtype=torch.int32)
+    with pytest.raises(ValueError):
+        oapl.logprob_fwd(H, W, tok)       # host tensors are refused, nothing is computed on the CPU
