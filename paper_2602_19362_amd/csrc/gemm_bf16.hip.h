@@ -1,10 +1,21 @@
 // bf16 MFMA contractions of the OAPL loss head, hand-written for gfx950.
 //
 // One main loop serves all four dense steps of the path.  It computes a
-// BM x BN tile of  C[m][n] = sum_k A[m][k] * B[n][k]  with both operands
-// K-contiguous ("NT" form), fp32 accumulation in v_mfma_f32_32x32x16_bf16,
-// operands streamed HBM/L2 -> LDS by direct-to-LDS buffer loads (no VGPR
-// staging) into a two-stage, XOR-swizzled LDS ring.
+// 256 x 256 tile of  C[m][n] = sum_k A[m][k] * B[n][k]  with both operands
+// k-contiguous, fp32 accumulation in v_mfma_f32_32x32x16_bf16, operands
+// streamed L2 -> LDS by direct-to-LDS buffer loads (no VGPR staging) into a
+// two-stage, XOR-swizzled LDS ring, 8 wavefronts (two per SIMD, so one
+// wavefront's waits are covered by the other's MFMAs).
+//
+// Operand layout in HBM ("packed"): a matrix with R rows and K columns is
+// stored as blocks of 256 rows x 64 columns, block (rt, kt) at byte offset
+// (rt * n_kt + kt) * 32 KiB, row-major inside the block (128 B per row), zero
+// padded to whole blocks.  One k-step of one tile is then ONE contiguous 32 KiB
+// read per operand (full 128-byte lines, sequential DRAM pages), instead of 256
+// row fragments spread over a 2 MB .. 80 MB span, and ragged edges need no
+// special case in the loads: padding is zeros.  The caller's row-major H and W
+// are packed once per call by k_pack_rows / k_pack_transposed; the kernels
+// that produce intermediate operands write them packed directly.
 //
 // In the accumulator of a 32x32 MFMA block a lane owns ONE column n (lane%32)
 // and 16 rows m: m = 8*(r/4) + 4*(lane/32) + r%4 for register r.  Every
@@ -12,29 +23,33 @@
 //   * forward (logits^T tile, M = vocabulary, N = tokens): the soft-max
 //     reduction over the vocabulary is lane-local, so the streaming max / sum
 //     needs no cross-lane traffic until the very end;
-//   * outputs that are row-major in n with m contiguous (dZ[t][v], dH[t][j],
-//     dW[v][j]) get 4 consecutive m per lane.
+//   * outputs with m contiguous (G[t][v], dH[t][j], dW[v][j]) get 4
+//     consecutive m per lane.
 #pragma once
 
 #include "common.hip.h"
 
 namespace oapl {
 
-template <int WM_, int WN_, int TM_, int TN_>
+constexpr int kPackRows = 256;                          // rows of a packed block
+constexpr int kPackK = 64;                              // k-extent of a packed block
+constexpr int kPackBlockBytes = kPackRows * kPackK * 2; // 32 KiB
+
+template <int WM_, int WN_, int TM_, int TN_, int NS_>
 struct TileCfg {
   static constexpr int WM = WM_, WN = WN_, TM = TM_, TN = TN_;
   static constexpr int NW = WM * WN;            // waves per workgroup
   static constexpr int NT = NW * 64;            // threads per workgroup
   static constexpr int BM = WM * TM * 32;
   static constexpr int BN = WN * TN * 32;
-  static constexpr int BK = 64;                 // k-extent of one LDS stage
-  static constexpr int ROW_BYTES = BK * 2;      // 128 B = 8 chunks of 16 B
-  static constexpr int A_STAGE = BM * ROW_BYTES;
-  static constexpr int B_STAGE = BN * ROW_BYTES;
-  static constexpr int B_OFF = 2 * A_STAGE;
-  static constexpr int MAIN_BYTES = 2 * (A_STAGE + B_STAGE);
-  static constexpr int NIA = BM / (8 * NW);     // direct loads per wave and stage, A
-  static constexpr int NIB = BN / (8 * NW);
+  static constexpr int BK = kPackK;             // k-extent of one LDS stage
+  static constexpr int NS = NS_;                // LDS stages in the ring
+  static constexpr int KSTEPS = BK / 16;        // MFMA k-steps per stage
+  static constexpr int ROW_BYTES = BK * 2;      // 128
+  static constexpr int STAGE = kPackBlockBytes; // one operand, one stage
+  static constexpr int B_OFF = NS * STAGE;
+  static constexpr int MAIN_BYTES = 2 * NS * STAGE;
+  static constexpr int NI = kPackRows / (8 * NW);  // direct loads per wave, operand and stage (8 rows each)
   // bf16 staging tiles used by epilogues (16 B of padding per row).
   static constexpr int PITCH_NM = BM * 2 + 16;  // tile stored [n][m]
   static constexpr int PITCH_MN = BN * 2 + 16;  // tile stored [m][n]
@@ -44,113 +59,85 @@ struct TileCfg {
   static constexpr int LDS_BYTES =
       MAIN_BYTES > STAGE_NM ? (MAIN_BYTES > STAGE_MN ? MAIN_BYTES : STAGE_MN)
                             : (STAGE_NM > STAGE_MN ? STAGE_NM : STAGE_MN);
-  static_assert(BM % (8 * NW) == 0 && BN % (8 * NW) == 0, "tile rows must split over waves");
+  static_assert(BM == kPackRows && BN == kPackRows, "tiles are one packed block tall");
+  static_assert(NS >= 2 && NS <= 2, "ring size");
+  static_assert(kPackRows % (8 * NW) == 0, "block rows must split over waves");
   static_assert(RED_BYTES <= LDS_BYTES, "reduction scratch must fit");
 };
 
 typedef __attribute__((address_space(3))) char* lds_char_ptr;
 
-// 16-byte chunk c of LDS row `row` lives at physical chunk c ^ ((row >> 1) & 7):
-// 16 consecutive rows read at one logical chunk then hit 16 distinct 16-byte
-// bank groups (rows alternate between the two 128-byte halves of the 256-byte
-// bank line, and the XOR spreads each half over its 8 groups).
-__device__ __forceinline__ int swz(int row) { return (row >> 1) & 7; }
+// s_waitcnt immediate for "at most n vector-memory operations still outstanding" (gfx9 encoding:
+// vmcnt in bits [3:0] and [15:14]; expcnt and lgkmcnt fields left at their maximum = no wait).
+__host__ __device__ constexpr int vmcnt_imm(int n) { return (n & 15) | ((n >> 4) << 14) | 0x0F70; }
 
 template <class C>
 struct Mainloop {
+  // 16-byte chunk c of LDS row `row` lives at physical chunk c ^ ((row >> 1) & 7).  The operand
+  // fetch of 16 consecutive rows at one logical chunk then touches 16 distinct 16-byte bank groups:
+  // two consecutive rows fill one 256-byte bank line, and the XOR walks each half's 8 slots.
+  static __device__ __forceinline__ int swz(int row) { return (row >> 1) & 7; }
+
   __amdgpu_buffer_rsrc_t ra, rb;
-  int voffA[C::NIA], voffB[C::NIB];   // per-lane byte offsets of this lane's chunk in the A / B tile
-  int chunkA[C::NIA], chunkB[C::NIB]; // logical 16-byte chunk index (0..7) the lane fetches
-  int rdA[4], rdB[4];                 // LDS byte offsets of this lane's operand fragment for k-step 0..3
+  int voff[C::NI];                    // per-lane byte offset of this lane's chunk inside a packed block
+  int rdA[C::KSTEPS], rdB[C::KSTEPS]; // LDS byte offsets of this lane's operand fragment per k-step
   int wave, lane;
 
-  // lda / ldb in elements.  Offsets depend only on the leading dimensions and
-  // the lane, so one setup serves every tile of a kernel.
-  __device__ __forceinline__ void setup(int64_t lda, int64_t ldb) {
+  __device__ __forceinline__ void setup() {
     const int tid = threadIdx.x;
     // the wave index feeds LDS base addresses that must live in scalar registers
     wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     lane = tid & 63;
     const int wm = wave / C::WN, wn = wave % C::WN;
 #pragma unroll
-    for (int i = 0; i < C::NIA; ++i) {
+    for (int i = 0; i < C::NI; ++i) {
+      // one wave-wide load covers 8 block rows; lane l lands at LDS byte l*16 of that 1 KiB
       const int row = (i * C::NW + wave) * 8 + (lane >> 3);
       const int c = (lane & 7) ^ swz(row);
-      chunkA[i] = c;
-      voffA[i] = (int)(row * lda * 2 + c * 16);
-    }
-#pragma unroll
-    for (int i = 0; i < C::NIB; ++i) {
-      const int row = (i * C::NW + wave) * 8 + (lane >> 3);
-      const int c = (lane & 7) ^ swz(row);
-      chunkB[i] = c;
-      voffB[i] = (int)(row * ldb * 2 + c * 16);
+      voff[i] = row * C::ROW_BYTES + c * 16;
     }
     const int rowA = wm * C::TM * 32 + (lane & 31);
     const int rowB = wn * C::TN * 32 + (lane & 31);
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks) {
+    for (int ks = 0; ks < C::KSTEPS; ++ks) {
       const int c = 2 * ks + (lane >> 5);
       rdA[ks] = rowA * C::ROW_BYTES + ((c ^ swz(rowA)) << 4);
       rdB[ks] = C::B_OFF + rowB * C::ROW_BYTES + ((c ^ swz(rowB)) << 4);
     }
   }
 
-  // A tile: rows [0, rows_valid) of a row-major matrix starting at `base`
-  // (already moved to the tile's first row, k = 0).  Rows past rows_valid and
-  // anything past the buffer read as zero (buffer range check).
-  __device__ __forceinline__ void set_a(const bf16_t* base, int64_t rows_valid, int64_t lda) {
-    const int64_t rv = rows_valid < C::BM ? (rows_valid < 0 ? 0 : rows_valid) : C::BM;
-    // num_records must sit in scalar registers (the clamp above may be done on the vector ALU)
-    ra = __builtin_amdgcn_make_buffer_rsrc((void*)base, 0, __builtin_amdgcn_readfirstlane((int)(rv * lda * 2)), 0x00020000);
+  // Operand = one row-tile strip of a packed matrix: n_kt consecutive 32 KiB blocks.
+  __device__ __forceinline__ void set_a(const bf16_t* strip, int n_kt) {
+    ra = __builtin_amdgcn_make_buffer_rsrc((void*)strip, 0, n_kt * kPackBlockBytes, 0x00020000);
   }
-  __device__ __forceinline__ void set_b(const bf16_t* base, int64_t rows_valid, int64_t ldb) {
-    const int64_t rv = rows_valid < C::BN ? (rows_valid < 0 ? 0 : rows_valid) : C::BN;
-    rb = __builtin_amdgcn_make_buffer_rsrc((void*)base, 0, __builtin_amdgcn_readfirstlane((int)(rv * ldb * 2)), 0x00020000);
+  __device__ __forceinline__ void set_b(const bf16_t* strip, int n_kt) {
+    rb = __builtin_amdgcn_make_buffer_rsrc((void*)strip, 0, n_kt * kPackBlockBytes, 0x00020000);
   }
 
-  // Starts the direct-to-LDS loads of the k-tile beginning at element k0 into
-  // `stage`.  `K` is only looked at when the k-tile is the ragged last one.
-  template <int STAGE>
-  __device__ __forceinline__ void issue(lds_char_ptr smem, int k0, int K) {
-    const int soff = k0 * 2;
-    if (k0 + C::BK <= K) {
+  // Starts the direct-to-LDS loads of k-block kt into ring slot STAGE (a literal at the call sites,
+  // so the LDS addresses fold to constants once inlined).
+  __device__ __forceinline__ void issue(const int STAGE, lds_char_ptr smem, int kt) {
+    const int soff = kt * kPackBlockBytes;
 #pragma unroll
-      for (int i = 0; i < C::NIA; ++i)
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(
-            ra, (lds_void_ptr)(smem + STAGE * C::A_STAGE + (i * C::NW + wave) * 1024), 16, voffA[i], soff, 0, 0);
+    for (int i = 0; i < C::NI; ++i)
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(
+          ra, (lds_void_ptr)(smem + STAGE * C::STAGE + (i * C::NW + wave) * 1024), 16, voff[i], soff, 0, 0);
 #pragma unroll
-      for (int i = 0; i < C::NIB; ++i)
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(
-            rb, (lds_void_ptr)(smem + C::B_OFF + STAGE * C::B_STAGE + (i * C::NW + wave) * 1024), 16, voffB[i], soff, 0, 0);
-    } else {
-      // ragged k-tile: chunks at or past K are sent out of range and come back as zeros
-#pragma unroll
-      for (int i = 0; i < C::NIA; ++i) {
-        const int v = (k0 + chunkA[i] * 8 < K) ? voffA[i] : 0x7FFFFF00;
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(
-            ra, (lds_void_ptr)(smem + STAGE * C::A_STAGE + (i * C::NW + wave) * 1024), 16, v, soff, 0, 0);
-      }
-#pragma unroll
-      for (int i = 0; i < C::NIB; ++i) {
-        const int v = (k0 + chunkB[i] * 8 < K) ? voffB[i] : 0x7FFFFF00;
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(
-            rb, (lds_void_ptr)(smem + C::B_OFF + STAGE * C::B_STAGE + (i * C::NW + wave) * 1024), 16, v, soff, 0, 0);
-      }
-    }
+    for (int i = 0; i < C::NI; ++i)
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(
+          rb, (lds_void_ptr)(smem + C::B_OFF + STAGE * C::STAGE + (i * C::NW + wave) * 1024), 16, voff[i], soff, 0, 0);
   }
 
-  template <int STAGE>
-  __device__ __forceinline__ void compute(lds_char_ptr smem, f32x16 (&acc)[C::TM][C::TN]) {
+  __device__ __forceinline__ void compute(const int STAGE, lds_char_ptr smem, f32x16 (&acc)[C::TM][C::TN]) {
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks) {
+    for (int ks = 0; ks < C::KSTEPS; ++ks) {
       bf16x8 a[C::TM], b[C::TN];
 #pragma unroll
       for (int i = 0; i < C::TM; ++i)
-        a[i] = *(const __attribute__((address_space(3))) bf16x8*)(smem + STAGE * C::A_STAGE + rdA[ks] + i * 32 * C::ROW_BYTES);
+        a[i] = *(const __attribute__((address_space(3))) bf16x8*)(smem + STAGE * C::STAGE + rdA[ks] + i * 32 * C::ROW_BYTES);
 #pragma unroll
       for (int j = 0; j < C::TN; ++j)
-        b[j] = *(const __attribute__((address_space(3))) bf16x8*)(smem + STAGE * C::B_STAGE + rdB[ks] + j * 32 * C::ROW_BYTES);
+        b[j] = *(const __attribute__((address_space(3))) bf16x8*)(smem + STAGE * C::STAGE + rdB[ks] + j * 32 * C::ROW_BYTES);
 #pragma unroll
       for (int i = 0; i < C::TM; ++i)
 #pragma unroll
@@ -159,33 +146,31 @@ struct Mainloop {
     }
   }
 
-  static __device__ __forceinline__ void wait_loads_and_sync() {
-    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wave's direct-to-LDS loads have landed
+  // One k-block of the pipeline in ring slot S (a literal at the call sites): wait until the block's
+  // loads have landed, barrier (which also tells that every wave is done with the other slot),
+  // refill the other slot with the next block, multiply.  Branches are wave-uniform and touch no
+  // accumulator.
+  __device__ __forceinline__ void step(const int S, lds_char_ptr smem, int kt, int nk, f32x16 (&acc)[C::TM][C::TN]) {
+    __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
     __syncthreads();
+    if (kt + 1 < nk) issue(S ^ 1, smem, kt + 1);
+    compute(S, smem, acc);
   }
 
-  // acc += A_tile * B_tile^T over k in [0, K).  Ends with a barrier: on return
-  // every wave is done reading LDS, so the caller may reuse it at once.
-  __device__ __forceinline__ void run(lds_char_ptr smem, int K, f32x16 (&acc)[C::TM][C::TN]) {
-    const int nk = (K + C::BK - 1) / C::BK;
-    issue<0>(smem, 0, K);
-    wait_loads_and_sync();
-    // Two k-tiles per trip so the stage index is a compile-time constant; an
-    // odd last k-tile is peeled off below.  The accumulators flow straight
-    // through (no early exit inside the loop).
+  // Starts a tile: k-block 0 into slot 0.  Every wave must be past its last LDS read of the
+  // previous tile (finish() ends with a barrier).
+  __device__ __forceinline__ void start(lds_char_ptr smem) { issue(0, smem, 0); }
+
+  // acc += A_tile * B_tile^T over k-blocks [0, nk) after start().  Ends with a barrier: on return
+  // every wave is done reading LDS, so the caller may reuse it (or start() the next tile) at once.
+  __device__ __forceinline__ void finish(lds_char_ptr smem, int nk, f32x16 (&acc)[C::TM][C::TN]) {
     int kt = 0;
     for (; kt + 2 <= nk; kt += 2) {
-      issue<1>(smem, (kt + 1) * C::BK, K);
-      compute<0>(smem, acc);
-      wait_loads_and_sync();
-      if (kt + 2 < nk) issue<0>(smem, (kt + 2) * C::BK, K);
-      compute<1>(smem, acc);
-      wait_loads_and_sync();
+      step(0, smem, kt, nk, acc);
+      step(1, smem, kt + 1, nk, acc);
     }
-    if (kt < nk) {
-      compute<0>(smem, acc);
-      __syncthreads();
-    }
+    if (kt < nk) step(0, smem, kt, nk, acc);
+    __syncthreads();
   }
 };
 
@@ -264,15 +249,29 @@ __device__ __forceinline__ void stage_mn(lds_char_ptr smem, const f32x16 (&acc)[
   }
 }
 
+// Staged [n][m] tile -> packed matrix whose rows are the n index and whose k index is m:
+// `strip` is block (n-tile, 0) of the destination, kb0 the first k-block (m0 / 64).  The whole
+// tile is written (the packed buffers are padded to whole tiles; padding must be zeros).
 template <class C>
-__device__ __forceinline__ void store_mn(lds_char_ptr smem, bf16_t* out, int64_t ldo, int64_t m_rows, int64_t n_cols) {
+__device__ __forceinline__ void store_nm_packed(lds_char_ptr smem, bf16_t* strip, int kb0) {
+  constexpr int CH = C::BM / 8;
+  char* dst = (char*)strip + (int64_t)kb0 * kPackBlockBytes;
+  for (int idx = threadIdx.x; idx < C::BN * CH; idx += C::NT) {
+    const int n_l = idx / CH, ch = idx % CH;
+    const u32x4 v = *(const __attribute__((address_space(3))) u32x4*)(smem + n_l * C::PITCH_NM + ch * 16);
+    *(u32x4*)(dst + (ch >> 3) * kPackBlockBytes + n_l * 128 + (ch & 7) * 16) = v;
+  }
+}
+
+// Staged [m][n] tile -> packed matrix whose rows are the m index and whose k index is n.
+template <class C>
+__device__ __forceinline__ void store_mn_packed(lds_char_ptr smem, bf16_t* strip, int kb0) {
   constexpr int CH = C::BN / 8;
+  char* dst = (char*)strip + (int64_t)kb0 * kPackBlockBytes;
   for (int idx = threadIdx.x; idx < C::BM * CH; idx += C::NT) {
     const int m_l = idx / CH, ch = idx % CH;
-    if (m_l < m_rows && ch * 8 < n_cols) {
-      const u32x4 v = *(const __attribute__((address_space(3))) u32x4*)(smem + m_l * C::PITCH_MN + ch * 16);
-      *(u32x4*)(out + (int64_t)m_l * ldo + ch * 8) = v;
-    }
+    const u32x4 v = *(const __attribute__((address_space(3))) u32x4*)(smem + m_l * C::PITCH_MN + ch * 16);
+    *(u32x4*)(dst + (ch >> 3) * kPackBlockBytes + m_l * 128 + (ch & 7) * 16) = v;
   }
 }
 
@@ -292,16 +291,18 @@ __device__ __forceinline__ void strip_tile(int L, int MT, int NTl, int& mt, int&
 // ---------------------------------------------------------------------------
 // Forward: logits^T tiles with a streaming (online) log-sum-exp over the
 // vocabulary.  The T x V logits never leave registers.
-//   A = W [V, d]  (M = vocabulary),  B = H [T, d]  (N = tokens),  K = d.
+//   A = packed W [V, d]  (M = vocabulary),  B = packed H [T, d]  (N = tokens),  K = d.
 // One workgroup owns one token tile and walks a contiguous range ("split") of
 // vocabulary tiles, carrying per token the running pair
 //     m2 = max_v z * log2(e),   s = sum_v 2^(z * log2(e) - m2)
-// and merging a new tile by the usual rescaling rule.  It writes one (m2, s)
-// pair per token and split; a later kernel merges the splits.
+// and merging a new tile by the usual rescaling rule.  The first k-block of
+// the next vocabulary tile is requested before the current tile's epilogue.
+// It writes one (m2, s) pair per token and split; a later kernel merges the
+// splits.
 // ---------------------------------------------------------------------------
 template <class C>
 __global__ void __launch_bounds__(C::NT)
-k_fwd_lse(const bf16_t* __restrict__ W, const bf16_t* __restrict__ H, int V, int64_t T, int d,
+k_fwd_lse(const bf16_t* __restrict__ Wp, const bf16_t* __restrict__ Hp, int V, int64_t T, int n_kt,
           int n_splits, float2* __restrict__ partials) {
   extern __shared__ __attribute__((aligned(1024))) char smem_raw[];
   lds_char_ptr smem = (lds_char_ptr)smem_raw;
@@ -315,10 +316,11 @@ k_fwd_lse(const bf16_t* __restrict__ W, const bf16_t* __restrict__ H, int V, int
   const int mt_begin = (int)((int64_t)split * MT / n_splits);
   const int mt_end = (int)((int64_t)(split + 1) * MT / n_splits);
   const int64_t n0 = (int64_t)nt * C::BN;
+  const int64_t strip_elems = (int64_t)n_kt * (kPackBlockBytes / 2);
 
   Mainloop<C> ml;
-  ml.setup(d, d);
-  ml.set_b(H + n0 * d, T - n0, d);
+  ml.setup();
+  ml.set_b(Hp + nt * strip_elems, n_kt);
 
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int wm = wave / C::WN, wn = wave % C::WN;
@@ -329,13 +331,20 @@ k_fwd_lse(const bf16_t* __restrict__ W, const bf16_t* __restrict__ H, int V, int
   for (int j = 0; j < C::TN; ++j) { m2[j] = kNegHuge; s[j] = 0.f; }
 
   f32x16 acc[C::TM][C::TN];
+  if (mt_begin < mt_end) {
+    ml.set_a(Wp + mt_begin * strip_elems, n_kt);
+    ml.start(smem);
+  }
   for (int mt = mt_begin; mt < mt_end; ++mt) {
     const int m0 = mt * C::BM;
-    ml.set_a(W + (int64_t)m0 * d, V - m0, d);
     zero_acc<C>(acc);
-    ml.run(smem, d, acc);
+    ml.finish(smem, n_kt, acc);
+    if (mt + 1 < mt_end) {  // the epilogue below works in registers only: overlap it with the next tile's first loads
+      ml.set_a(Wp + (mt + 1) * strip_elems, n_kt);
+      ml.start(smem);
+    }
 
-    if (m0 + C::BM > V) {  // ragged last vocabulary tile: rows >= V do not exist
+    if (m0 + C::BM > V) {  // ragged last vocabulary tile: rows >= V do not exist (their logits are 0, not -inf)
       const int row0 = m0 + wm * C::TM * 32 + 4 * h;
 #pragma unroll
       for (int i = 0; i < C::TM; ++i)
@@ -405,18 +414,17 @@ k_fwd_lse(const bf16_t* __restrict__ W, const bf16_t* __restrict__ H, int V, int
 // entries (tiny, with uncorrelated roundings) carry no common factor, so no
 // rounding error is shared by all tokens of a rollout.  The fp32 row factor f_t
 // is applied by the consumers: dH = diag(f) (G W), dW = G^T (diag(f) H).
-// G is written twice, for one panel of Tp token rows:
-//     dZ  [Tp][Vp]  (v contiguous)   -> dH
-//     dZT [V][Tp]   (t contiguous)   -> dW
-// Rows / columns outside the valid ranges are written as zeros so the
-// consumers can read whole tiles.
-//   A = W [V, d] (M = vocabulary), B = H panel [n_valid, d] (N = tokens).
+// G is written twice, packed, for one panel of token rows:
+//     Gp   rows = tokens,      k = vocabulary   -> B operand of the dH contraction
+//     GTp  rows = vocabulary,  k = tokens       -> B operand of the dW contraction
+// Entries outside the valid ranges are written as zeros (whole tiles are stored).
+//   A = packed W (M = vocabulary), B = packed H, panel's first token tile (N = tokens).
 // ---------------------------------------------------------------------------
 template <class C>
 __global__ void __launch_bounds__(C::NT)
-k_bwd_dz(const bf16_t* __restrict__ W, const bf16_t* __restrict__ Hp, int V, int64_t n_valid, int d,
+k_bwd_dz(const bf16_t* __restrict__ Wp, const bf16_t* __restrict__ Hp_panel, int V, int64_t n_valid, int n_kt,
          const int32_t* __restrict__ tokens, const float* __restrict__ lse2, const float* __restrict__ inv_omp,
-         bf16_t* __restrict__ dZ, int64_t Vp, bf16_t* __restrict__ dZT, int64_t Tp) {
+         bf16_t* __restrict__ Gp, int g_n_kt, bf16_t* __restrict__ GTp, int gt_n_kt) {
   extern __shared__ __attribute__((aligned(1024))) char smem_raw[];
   lds_char_ptr smem = (lds_char_ptr)smem_raw;
 
@@ -429,15 +437,17 @@ k_bwd_dz(const bf16_t* __restrict__ W, const bf16_t* __restrict__ Hp, int V, int
   strip_tile<8>(L, MT, NTl, mt, nt);
   const int m0 = mt * C::BM;
   const int64_t n0 = (int64_t)nt * C::BN;
+  const int64_t strip_elems = (int64_t)n_kt * (kPackBlockBytes / 2);
 
   Mainloop<C> ml;
-  ml.setup(d, d);
-  ml.set_a(W + (int64_t)m0 * d, V - m0, d);
-  ml.set_b(Hp + n0 * d, n_valid - n0, d);
+  ml.setup();
+  ml.set_a(Wp + mt * strip_elems, n_kt);
+  ml.set_b(Hp_panel + nt * strip_elems, n_kt);
 
   f32x16 acc[C::TM][C::TN];
   zero_acc<C>(acc);
-  ml.run(smem, d, acc);
+  ml.start(smem);
+  ml.finish(smem, n_kt, acc);
 
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int wm = wave / C::WN, wn = wave % C::WN;
@@ -490,28 +500,25 @@ k_bwd_dz(const bf16_t* __restrict__ W, const bf16_t* __restrict__ Hp, int V, int
         }
   }
 
-  // dZ[t][v]: stage [n][m], then 16-byte row stores
+  // Gp: rows = tokens (n), k = vocabulary (m)
   stage_nm<C>(smem, acc);
   __syncthreads();
-  {
-    const int64_t rows = n_valid - n0;
-    const int64_t cols = Vp - m0;
-    store_nm<C>(smem, dZ + n0 * Vp + m0, Vp, rows, cols);
-  }
+  store_nm_packed<C>(smem, Gp + (int64_t)nt * g_n_kt * (kPackBlockBytes / 2), m0 / kPackK);
   __syncthreads();
-  // dZT[v][t]: stage [m][n]; all BN columns are written (zeros past n_valid)
+  // GTp: rows = vocabulary (m), k = tokens (n)
   stage_mn<C>(smem, acc);
   __syncthreads();
-  store_mn<C>(smem, dZT + (int64_t)m0 * Tp + n0, Tp, (int64_t)V - m0, C::BN);
+  store_mn_packed<C>(smem, GTp + (int64_t)mt * gt_n_kt * (kPackBlockBytes / 2), (int)(n0 / kPackK));
 }
 
 // ---------------------------------------------------------------------------
 // Backward, step 2: dH[t][j] = f_t * sum_v G[t][v] * W[v][j]
-//   A = WT [d][Vp] (M = hidden index j), B = dZ panel [n_valid][Vp] (N = tokens), K = V.
+//   A = packed W^T (rows = hidden index j, k = vocabulary), B = Gp (rows = tokens), K = V.
 // ---------------------------------------------------------------------------
 template <class C>
 __global__ void __launch_bounds__(C::NT)
-k_bwd_dh(const bf16_t* __restrict__ WT, const bf16_t* __restrict__ dZ, int d, int64_t n_valid, int V, int64_t Vp,
+k_bwd_dh(const bf16_t* __restrict__ WTp, int wt_n_kt, const bf16_t* __restrict__ Gp, int g_n_kt, int d,
+         int64_t n_valid, int nk /* k-blocks to contract: ceil(V / 64) */,
          const float* __restrict__ row_factor /* f_t, panel-local */, bf16_t* __restrict__ dH /* panel's first row */) {
   extern __shared__ __attribute__((aligned(1024))) char smem_raw[];
   lds_char_ptr smem = (lds_char_ptr)smem_raw;
@@ -527,13 +534,14 @@ k_bwd_dh(const bf16_t* __restrict__ WT, const bf16_t* __restrict__ dZ, int d, in
   const int64_t n0 = (int64_t)nt * C::BN;
 
   Mainloop<C> ml;
-  ml.setup(Vp, Vp);
-  ml.set_a(WT + (int64_t)m0 * Vp, d - m0, Vp);
-  ml.set_b(dZ + n0 * Vp, n_valid - n0, Vp);
+  ml.setup();
+  ml.set_a(WTp + (int64_t)mt * wt_n_kt * (kPackBlockBytes / 2), wt_n_kt);
+  ml.set_b(Gp + (int64_t)nt * g_n_kt * (kPackBlockBytes / 2), g_n_kt);
 
   f32x16 acc[C::TM][C::TN];
   zero_acc<C>(acc);
-  ml.run(smem, V, acc);
+  ml.start(smem);
+  ml.finish(smem, nk, acc);
 
   {
     const int lane = threadIdx.x & 63, wn = (threadIdx.x >> 6) % C::WN;
@@ -552,13 +560,13 @@ k_bwd_dh(const bf16_t* __restrict__ WT, const bf16_t* __restrict__ dZ, int d, in
 
 // ---------------------------------------------------------------------------
 // Backward, step 3: dW[v][j] (+)= sum_t G[t][v] * (f_t H[t][j])
-//   A = HT [d][Tp] = (diag(f) H)^T (M = hidden index j), B = dZT [V][Tp] (N = vocabulary), K = Kt
-//   (the panel's token count rounded up to the tile; the padding is zeros).
+//   A = packed (diag(f) H)^T (rows = hidden index j, k = panel tokens), B = GTp (rows = vocabulary).
 // fp32 output written straight from the accumulators: 4 consecutive j per lane.
 // ---------------------------------------------------------------------------
 template <class C>
 __global__ void __launch_bounds__(C::NT)
-k_bwd_dw(const bf16_t* __restrict__ HT, const bf16_t* __restrict__ dZT, int d, int V, int64_t Tp, int Kt,
+k_bwd_dw(const bf16_t* __restrict__ HTp, const bf16_t* __restrict__ GTp, int t_n_kt /* strip pitch of both */, int d,
+         int V, int nk /* k-blocks to contract: panel tokens / 64, rounded up to the tile */,
          float* __restrict__ dW, int accumulate) {
   extern __shared__ __attribute__((aligned(1024))) char smem_raw[];
   lds_char_ptr smem = (lds_char_ptr)smem_raw;
@@ -574,13 +582,14 @@ k_bwd_dw(const bf16_t* __restrict__ HT, const bf16_t* __restrict__ dZT, int d, i
   const int n0 = nt * C::BN;
 
   Mainloop<C> ml;
-  ml.setup(Tp, Tp);
-  ml.set_a(HT + (int64_t)m0 * Tp, d - m0, Tp);
-  ml.set_b(dZT + (int64_t)n0 * Tp, V - n0, Tp);
+  ml.setup();
+  ml.set_a(HTp + (int64_t)mt * t_n_kt * (kPackBlockBytes / 2), t_n_kt);
+  ml.set_b(GTp + (int64_t)nt * t_n_kt * (kPackBlockBytes / 2), t_n_kt);
 
   f32x16 acc[C::TM][C::TN];
   zero_acc<C>(acc);
-  ml.run(smem, Kt, acc);
+  ml.start(smem);
+  ml.finish(smem, nk, acc);
 
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int wm = wave / C::WN, wn = wave % C::WN;
@@ -606,6 +615,69 @@ k_bwd_dw(const bf16_t* __restrict__ HT, const bf16_t* __restrict__ dZT, int d, i
           *p = v;
         }
       }
+  }
+}
+
+// ---------------------------------------------------------------------------
+// Packing of row-major matrices into the block layout the main loop reads.
+// ---------------------------------------------------------------------------
+
+// dst = packed(src), src [R, K] row-major with leading dimension ld (K and ld multiples of 8).
+// One workgroup per 256 x 64 block; blocks in [0, n_rt) x [0, n_kt); everything outside
+// [0, R) x [0, K) is written as zero.
+__global__ void __launch_bounds__(256)
+k_pack_rows(const bf16_t* __restrict__ src, int64_t R, int K, int64_t ld, bf16_t* __restrict__ dst, int n_kt) {
+  const int kt = blockIdx.x;
+  const int64_t rt = blockIdx.y;
+  char* out = (char*)dst + (rt * n_kt + kt) * (int64_t)kPackBlockBytes;
+#pragma unroll
+  for (int it = 0; it < 8; ++it) {
+    const int idx = it * 256 + threadIdx.x;       // 2048 chunks of 16 B
+    const int row = idx >> 3, c = idx & 7;
+    const int64_t r = rt * kPackRows + row;
+    const int k = kt * kPackK + c * 8;
+    u32x4 v = {0u, 0u, 0u, 0u};
+    if (r < R && k < K) v = *(const u32x4*)(src + r * ld + k);
+    *(u32x4*)(out + row * 128 + c * 16) = v;
+  }
+}
+
+// dst = packed(S^T) where S [R, Ccols] is row-major (ld) and optionally row-scaled:
+// dst row j (a column of S), k index r (a row of S): dst(j, r) = bf16(S[r][j] * scale[r]).
+// One workgroup per destination block (jt, kt): it reads S[kt*64 .. +64][jt*256 .. +256]
+// through LDS.  Blocks in [0, n_jt) x [0, n_kt); zero outside [0, Ccols) x [0, R).
+__global__ void __launch_bounds__(256)
+k_pack_transposed(const bf16_t* __restrict__ src, int64_t R, int Ccols, int64_t ld, const float* __restrict__ scale,
+                  bf16_t* __restrict__ dst, int n_kt) {
+  __shared__ bf16_t tile[64][kPackRows + 2];
+  const int kt = blockIdx.x, jt = blockIdx.y;
+  const int64_t r0 = (int64_t)kt * kPackK;
+  const int j0 = jt * kPackRows;
+  for (int i = threadIdx.x >> 6; i < 64; i += 4) {          // 4 source rows per pass, 64 lanes x 4 columns each
+    const int64_t r = r0 + i;
+    const float sc = (scale != nullptr && r < R) ? scale[r] : 1.f;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int jl = (threadIdx.x & 63) + q * 64;
+      const int j = j0 + jl;
+      bf16_t v = (bf16_t)0.f;
+      if (r < R && j < Ccols) {
+        v = src[r * ld + j];
+        if (scale != nullptr) v = (bf16_t)((float)v * sc);
+      }
+      tile[i][jl] = v;
+    }
+  }
+  __syncthreads();
+  char* out = (char*)dst + ((int64_t)jt * n_kt + kt) * (int64_t)kPackBlockBytes;
+#pragma unroll
+  for (int it = 0; it < 8; ++it) {
+    const int idx = it * 256 + threadIdx.x;
+    const int row = idx >> 3, c = idx & 7;                  // destination row (j), 8 consecutive k
+    bf16x8 v;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) v[e] = tile[c * 8 + e][row];
+    *(bf16x8*)(out + row * 128 + c * 16) = v;
   }
 }
 

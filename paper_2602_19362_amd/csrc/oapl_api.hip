@@ -14,12 +14,12 @@
 
 namespace oapl {
 
-// 256 x 256 x 64 tiles, 4 wavefronts in a 2 x 2 grid, each a 128 x 128 patch
-// (4 x 4 MFMA blocks): 256 accumulator registers per lane, one wavefront per
-// SIMD, 128 KB of LDS for the two operand stages.
-typedef TileCfg<2, 2, 4, 4> Cfg;
+// 256 x 256 x 64 tiles, 8 wavefronts in a 4 x 2 grid, each a 64 x 128 patch
+// (2 x 4 MFMA blocks, 128 accumulator registers per lane), two wavefronts per
+// SIMD; operands in a ring of 2 LDS stages (128 KB).
+typedef TileCfg<4, 2, 2, 4, 2> Cfg;
 
-constexpr int64_t kPanelBf16 = 16384;  // token rows per backward panel (bf16 path)
+constexpr int64_t kPanelBf16 = 65536;  // most token rows per backward panel (bf16 path)
 constexpr int64_t kPanelF32 = 4096;    // ... (fp32 path)
 constexpr int kStatusWords = 64;       // 256-byte header
 
@@ -31,9 +31,12 @@ struct Plan {
   bool bwd = false;
   int n_parts = 0;     // soft-max partials per token
   int64_t Tp = 0;      // rows of one backward panel
-  int64_t Vp = 0;      // row pitch of the dZ panel
+  // packed-operand geometry (bf16 path): row tiles and k-blocks (strip pitches)
+  int n_rt_v = 0, n_rt_d = 0, n_kt_d = 0, n_kt_v = 0, n_kt_g = 0, n_kt_t = 0;
+  int64_t n_rt_T = 0;
   size_t off_status = 0, off_partials = 0, off_zy = 0, off_lse2 = 0, off_diff = 0, off_coef = 0, off_delta = 0,
-         off_cseq = 0, off_vstar = 0, off_omp = 0, off_inv = 0, off_WT = 0, off_HT = 0, off_dZ = 0, off_dZT = 0, total = 0;
+         off_cseq = 0, off_vstar = 0, off_omp = 0, off_inv = 0, off_Wp = 0, off_Hp = 0, off_WTp = 0, off_HTp = 0,
+         off_G = 0, off_GT = 0, total = 0;
 };
 
 static bool make_plan(Plan& p, int64_t T, int d, int V, int n_seq, int n_groups, int dtype, bool bwd) {
@@ -51,12 +54,20 @@ static bool make_plan(Plan& p, int64_t T, int d, int V, int n_seq, int n_groups,
     if (splits > 64) splits = 64;
     if (splits < 1) splits = 1;
     p.n_parts = (int)splits;
-    p.Tp = T < kPanelBf16 ? round_up(T > 0 ? T : 1, Cfg::BN) : kPanelBf16;
-    p.Vp = round_up(V, 8);
+    // equal panels of at most kPanelBf16 rows (a short last panel would waste a whole pass
+    // of the fp32 read-add-write over dW)
+    const int64_t n_panels = T > 0 ? (T + kPanelBf16 - 1) / kPanelBf16 : 1;
+    p.Tp = round_up(T > 0 ? (T + n_panels - 1) / n_panels : 1, Cfg::BN);
+    p.n_rt_v = MT;
+    p.n_rt_d = (d + kPackRows - 1) / kPackRows;
+    p.n_rt_T = n_tiles > 0 ? n_tiles : 1;
+    p.n_kt_d = (d + kPackK - 1) / kPackK;
+    p.n_kt_v = (V + kPackK - 1) / kPackK;            // W^T strips: exactly the k-blocks the dH contraction walks
+    p.n_kt_g = MT * (kPackRows / kPackK);            // G strips: whole vocabulary tiles
+    p.n_kt_t = (int)(p.Tp / kPackK);                 // strips whose k index is the panel token
   } else {
     p.n_parts = (V + 63) / 64;
     p.Tp = T < kPanelF32 ? (T > 0 ? T : 1) : kPanelF32;
-    p.Vp = V;
   }
   size_t o = 0;
   auto take = [&](size_t bytes) { size_t at = o; o += (bytes + 255) / 256 * 256; return at; };
@@ -72,14 +83,18 @@ static bool make_plan(Plan& p, int64_t T, int d, int V, int n_seq, int n_groups,
   p.off_delta = take((size_t)(n_seq > 0 ? n_seq : 1) * 8);
   p.off_cseq = take((size_t)(n_seq > 0 ? n_seq : 1) * 4);
   p.off_vstar = take((size_t)n_groups * 8);
+  if (dtype == OAPL_BF16) {
+    p.off_Wp = take((size_t)p.n_rt_v * p.n_kt_d * kPackBlockBytes);
+    p.off_Hp = take((size_t)p.n_rt_T * p.n_kt_d * kPackBlockBytes);
+  }
   if (bwd) {
     if (dtype == OAPL_BF16) {
-      p.off_WT = take((size_t)d * p.Vp * 2);
-      p.off_HT = take((size_t)d * p.Tp * 2);
-      p.off_dZ = take((size_t)p.Tp * p.Vp * 2);
-      p.off_dZT = take((size_t)V * p.Tp * 2);
+      p.off_WTp = take((size_t)p.n_rt_d * p.n_kt_v * kPackBlockBytes);
+      p.off_HTp = take((size_t)p.n_rt_d * p.n_kt_t * kPackBlockBytes);
+      p.off_G = take((size_t)(p.Tp / kPackRows) * p.n_kt_g * kPackBlockBytes);
+      p.off_GT = take((size_t)p.n_rt_v * p.n_kt_t * kPackBlockBytes);
     } else {
-      p.off_dZ = take((size_t)p.Tp * p.Vp * 4);
+      p.off_G = take((size_t)p.Tp * V * 4);
     }
   }
   p.total = o;
@@ -162,12 +177,18 @@ static int forward_scores(const Plan& p, const void* H, const void* W, const int
     k_gather_logit<bf16_t, float><<<grid1d(T, 4), 256, 0, st>>>((const bf16_t*)H, (const bf16_t*)W, tokens, T, p.d,
                                                                 p.V, zy, status);
     OAPL_LAUNCH_CHECK();
+    bf16_t* Wp = (bf16_t*)(ws + p.off_Wp);
+    bf16_t* Hp = (bf16_t*)(ws + p.off_Hp);
+    k_pack_rows<<<dim3(p.n_kt_d, p.n_rt_v), 256, 0, st>>>((const bf16_t*)W, p.V, p.d, p.d, Wp, p.n_kt_d);
+    OAPL_LAUNCH_CHECK();
+    k_pack_rows<<<dim3(p.n_kt_d, (unsigned)p.n_rt_T), 256, 0, st>>>((const bf16_t*)H, T, p.d, p.d, Hp, p.n_kt_d);
+    OAPL_LAUNCH_CHECK();
     const int64_t n_tiles = (T + Cfg::BN - 1) / Cfg::BN;
     const int64_t total = n_tiles * p.n_parts;
     {
       ScopedKernelTimer tm(kFwdLse, st);
-      k_fwd_lse<Cfg><<<(unsigned)round_up(total, 8), Cfg::NT, Cfg::LDS_BYTES, st>>>(
-          (const bf16_t*)W, (const bf16_t*)H, p.V, T, p.d, p.n_parts, partials);
+      k_fwd_lse<Cfg><<<(unsigned)round_up(total, 8), Cfg::NT, Cfg::LDS_BYTES, st>>>(Wp, Hp, p.V, T, p.n_kt_d,
+                                                                                    p.n_parts, partials);
     }
     OAPL_LAUNCH_CHECK();
     k_lse_finish<true><<<grid1d(T, 256), 256, 0, st>>>(partials, p.n_parts, T, zy, logq, logprob_out, lse_out, lse2,
@@ -203,47 +224,46 @@ static int backward_grads(const Plan& p, const void* H, const void* W, const int
     return OAPL_OK;
   }
   if (p.dtype == OAPL_BF16) {
-    bf16_t* WT = (bf16_t*)(ws + p.off_WT);
-    bf16_t* HT = (bf16_t*)(ws + p.off_HT);
-    bf16_t* dZ = (bf16_t*)(ws + p.off_dZ);
-    bf16_t* dZT = (bf16_t*)(ws + p.off_dZT);
-    {
-      dim3 grid(grid1d(p.Vp, 64), grid1d(d, 64));
-      k_transpose_bf16<<<grid, 256, 0, st>>>((const bf16_t*)W, V, d, d, nullptr, WT, p.Vp, p.Vp);
-      OAPL_LAUNCH_CHECK();
-    }
-    const int MTv = (V + Cfg::BM - 1) / Cfg::BM, MTd = (d + Cfg::BM - 1) / Cfg::BM;
+    const bf16_t* Wp = (const bf16_t*)(ws + p.off_Wp);   // packed by the forward pass of this call
+    const bf16_t* Hp = (const bf16_t*)(ws + p.off_Hp);
+    bf16_t* WTp = (bf16_t*)(ws + p.off_WTp);
+    bf16_t* HTp = (bf16_t*)(ws + p.off_HTp);
+    bf16_t* G = (bf16_t*)(ws + p.off_G);
+    bf16_t* GT = (bf16_t*)(ws + p.off_GT);
+    k_pack_transposed<<<dim3(p.n_kt_v, p.n_rt_d), 256, 0, st>>>((const bf16_t*)W, V, d, d, nullptr, WTp, p.n_kt_v);
+    OAPL_LAUNCH_CHECK();
+    const int MTv = p.n_rt_v, MTd = p.n_rt_d;
+    const int64_t strip_d = (int64_t)p.n_kt_d * (kPackBlockBytes / 2);
     for (int64_t t0 = 0; t0 < T; t0 += p.Tp) {
       const int64_t nv = (T - t0) < p.Tp ? (T - t0) : p.Tp;
       const int64_t Kt = round_up(nv, Cfg::BN);
-      const bf16_t* Hp = (const bf16_t*)H + t0 * d;
-      const int64_t NTl = (nv + Cfg::BN - 1) / Cfg::BN;
-      {
-        dim3 grid(grid1d(Kt, 64), grid1d(d, 64));
-        k_transpose_bf16<<<grid, 256, 0, st>>>(Hp, nv, d, d, coef + t0, HT, p.Tp, Kt);
-        OAPL_LAUNCH_CHECK();
-      }
+      const int64_t NTl = Kt / Cfg::BN;
+      // (diag(f) H)^T of this panel, packed; token columns in [nv, Kt) come out as zeros
+      k_pack_transposed<<<dim3((unsigned)(Kt / kPackK), p.n_rt_d), 256, 0, st>>>(
+          (const bf16_t*)H + t0 * d, nv, d, d, coef + t0, HTp, p.n_kt_t);
+      OAPL_LAUNCH_CHECK();
       {
         ScopedKernelTimer tm(kBwdDz, st);
         k_bwd_dz<Cfg><<<(unsigned)round_up(MTv * NTl, 8), Cfg::NT, Cfg::LDS_BYTES, st>>>(
-            (const bf16_t*)W, Hp, V, nv, d, tokens + t0, lse2 + t0, inv + t0, dZ, p.Vp, dZT, p.Tp);
+            Wp, Hp + (t0 / kPackRows) * strip_d, V, nv, p.n_kt_d, tokens + t0, lse2 + t0, inv + t0, G, p.n_kt_g, GT,
+            p.n_kt_t);
       }
       OAPL_LAUNCH_CHECK();
       {
         ScopedKernelTimer tm(kBwdDh, st);
         k_bwd_dh<Cfg><<<(unsigned)round_up(MTd * NTl, 8), Cfg::NT, Cfg::LDS_BYTES, st>>>(
-            WT, dZ, d, nv, V, p.Vp, coef + t0, (bf16_t*)dH + t0 * d);
+            WTp, p.n_kt_v, G, p.n_kt_g, d, nv, p.n_kt_v, coef + t0, (bf16_t*)dH + t0 * d);
       }
       OAPL_LAUNCH_CHECK();
       {
         ScopedKernelTimer tm(kBwdDw, st);
         k_bwd_dw<Cfg><<<(unsigned)round_up((int64_t)MTd * MTv, 8), Cfg::NT, Cfg::LDS_BYTES, st>>>(
-            HT, dZT, d, V, p.Tp, (int)Kt, dW, t0 > 0 ? 1 : 0);
+            HTp, GT, p.n_kt_t, d, V, (int)(Kt / kPackK), dW, t0 > 0 ? 1 : 0);
       }
       OAPL_LAUNCH_CHECK();
     }
   } else {
-    float* dZ = (float*)(ws + p.off_dZ);
+    float* dZ = (float*)(ws + p.off_G);
     for (int64_t t0 = 0; t0 < T; t0 += p.Tp) {
       const int64_t nv = (T - t0) < p.Tp ? (T - t0) : p.Tp;
       const float* Hp = (const float*)H + t0 * d;

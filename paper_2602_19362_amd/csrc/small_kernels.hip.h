@@ -1,7 +1,6 @@
 // The O(T) and O(N) steps of the OAPL loss head: sampled-token logit gather,
 // log-sum-exp finish, per-rollout segmented sums, group value estimate and
-// loss (Sec. 3.1, Eq. 2 and Eq. 3), token coefficients, and the operand
-// transposes used by the backward GEMMs.  All bandwidth-trivial next to the
+// loss (Sec. 3.1, Eq. 2 and Eq. 3) and token coefficients.  All bandwidth-trivial next to the
 // three V x d contractions; written for exactness and a fixed summation order.
 #pragma once
 
@@ -196,31 +195,6 @@ k_token_coefficients(const float* __restrict__ cseq, const int64_t* __restrict__
   b = b < a ? a : (b > Ttok ? Ttok : b);
   const float c = cseq[s];
   for (int64_t t = a + threadIdx.x; t < b; t += 256) coef[t] = factor ? c * factor[t] : c;
-}
-
-// dst[c][r] = src[r][c] * (row_scale ? row_scale[r] : 1) for r < rows, c < cols;
-// dst has `dst_ld` columns and columns in [rows, zero_to) are cleared.  64 x 64
-// tiles through LDS.  A scaled element is rounded to bf16 once (nearest even).
-__global__ void __launch_bounds__(256)
-k_transpose_bf16(const bf16_t* __restrict__ src, int64_t rows, int64_t cols, int64_t src_ld,
-                 const float* __restrict__ row_scale, bf16_t* __restrict__ dst, int64_t dst_ld, int64_t zero_to) {
-  __shared__ bf16_t tile[64][66];
-  const int64_t r0 = (int64_t)blockIdx.x * 64, c0 = (int64_t)blockIdx.y * 64;
-  const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
-  for (int i = ty; i < 64; i += 4) {
-    const int64_t r = r0 + i, c = c0 + tx;
-    bf16_t v = (bf16_t)0.f;
-    if (r < rows && c < cols) {
-      v = src[r * src_ld + c];
-      if (row_scale) v = (bf16_t)((float)v * row_scale[r]);
-    }
-    tile[i][tx] = v;
-  }
-  __syncthreads();
-  for (int i = ty; i < 64; i += 4) {
-    const int64_t c = c0 + i, r = r0 + tx;
-    if (c < cols && r < zero_to) dst[c * dst_ld + r] = tile[tx][i];
-  }
 }
 
 }  // namespace oapl

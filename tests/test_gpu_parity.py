@@ -104,8 +104,8 @@ def test_bf16_ragged_shapes(d, V, lens, seed):
 
 
 def test_bf16_several_backward_panels():
-    """T spans three backward panels (16384 rows each), the last one ragged."""
-    lens = [16384, 9000, 7384 + 5000, 233]
+    """T = 150 001 spans three backward panels (at most 65 536 rows each), the last one ragged."""
+    lens = [65536, 9000, 40000, 233, 35232, 0]
     b = _custom_batch("bf16", d=64, V=520, lens=lens, n_groups=2, seed=5, beta=1.0, noise=0.02)
     res = _run(b)
     ref = oracle_full(b)
