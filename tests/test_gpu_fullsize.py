@@ -1,0 +1,147 @@
+"""Full-size runs of the four bf16 configurations, in the launch configuration bench.py times.
+
+A full fp64 oracle pass is out of reach at these sizes (6 T V d is 5e14 .. 4e15 flop), so each
+configuration is checked in three layers on the same seeded inputs:
+
+ (A) PARITY on sampled outputs the oracle computes one by one: per-token log-probs at a few hundred
+     token rows (first and last token of every rollout, rows around tile and panel edges, random
+     rows), and the group value estimates (all of them; they depend on rewards only).
+ (B) PARITY of every output, element by element, on a slice of the same configuration (same d, V,
+     dtype, weights; four rollouts cut to 256 tokens) that the oracle can do in full: log-probs,
+     log-ratios, loss, every element of dH and dW, gradient norm.
+ (C) PROPERTIES that hold at any size, checked on the full-size outputs (these are consistency
+     checks, not parity claims): the per-rollout log-ratio equals the segment sum of the exported
+     log-probs minus logq (every token -> rollout map exact), the loss equals the sum of squared
+     residuals built from those log-ratios and the oracle's value estimates, sampled dH rows equal
+     the oracle's row formula with the coefficient of the owning rollout, the columns of dW sum to
+     zero, <dH, H> = <dW, W>, and the gradients are finite.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import oapl_oracle as orc
+from paper_2602_19362_amd import oapl, synth
+from tests._util import f64, grad_norm, rel
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+PANEL_ROWS = 65536      # the library's largest backward panel; rows around its multiples are sampled
+
+
+def _sample_rows(off, T, n_random, seed):
+    rows = set()
+    for s in range(len(off) - 1):
+        if off[s + 1] > off[s]:
+            rows.add(int(off[s]))
+            rows.add(int(off[s + 1] - 1))
+    for edge in (0, 255, 256, 257, 511, 512, T - 257, T - 256, T - 1):
+        if 0 <= edge < T:
+            rows.add(int(edge))
+    for k in range(1, T // PANEL_ROWS + 1):
+        for e in (k * PANEL_ROWS - 1, k * PANEL_ROWS, k * PANEL_ROWS + 1):
+            if 0 <= e < T:
+                rows.add(int(e))
+    rng = np.random.default_rng(seed)
+    rows.update(int(x) for x in rng.integers(0, T, size=n_random))
+    return np.array(sorted(rows), dtype=np.int64)
+
+
+def _segment_sums(x64, off_t):
+    c = torch.zeros(x64.numel() + 1, dtype=torch.float64, device=x64.device)
+    c[1:] = torch.cumsum(x64, 0)
+    return (c[off_t[1:]] - c[off_t[:-1]]).cpu().numpy()
+
+
+def _slice_batch(b, n_roll=4, cut=256):
+    """The first n_roll rollouts of the batch, each cut to `cut` tokens; same W, beta, group ids."""
+    off = b.seq_offsets.cpu().numpy()
+    take = np.minimum(np.diff(off)[:n_roll], cut)
+    rows = np.concatenate([np.arange(off[s], off[s] + take[s]) for s in range(n_roll)])
+    rt = torch.from_numpy(rows).to(DEV)
+    new_off = torch.from_numpy(np.concatenate([[0], np.cumsum(take)]).astype(np.int64)).to(DEV)
+    rewards = b.rewards[:n_roll].clone()
+    if float(rewards.min()) == float(rewards.max()):
+        rewards[0] = 1.0 - rewards[0]          # keep the slice's value estimate non-degenerate
+    return synth.RolloutBatch(cfg=b.cfg, H=b.H[rt].contiguous(), W=b.W, tokens=b.tokens[rt].contiguous(),
+                              logq=b.logq[rt].contiguous(), seq_offsets=new_off, rewards=rewards,
+                              group_ids=torch.zeros(n_roll, dtype=torch.int32, device=DEV), beta=b.beta)
+
+
+@pytest.mark.parametrize("name", ["qwen1p7b_fwd", "qwen7b", "r1_14b", "long_rollout"])
+def test_full_size_configuration(name):
+    cfg = synth.CONFIGS[name]
+    b = synth.make_batch(cfg, DEV)
+    T, d, V = b.T, cfg.d, cfg.V
+    print(f"[{name}] T={T} d={d} V={V}", flush=True)
+    res = oapl.loss_fwd_bwd(b.H, b.W, b.tokens, b.logq, b.seq_offsets, b.rewards, b.group_ids, b.n_groups,
+                            b.beta, backward=cfg.backward)
+    torch.cuda.synchronize()
+    assert oapl.read_device_status(res.workspace) == 0
+    off = b.seq_offsets.cpu().numpy()
+    W64 = f64(b.W)
+
+    # ---- (A) sampled parity -------------------------------------------------------------------
+    rows = _sample_rows(off, T, n_random=192, seed=cfg.seed_index)
+    rt = torch.from_numpy(rows).to(DEV)
+    lp_ref, _ = orc.token_logprobs(f64(b.H[rt]), W64, b.tokens[rt].cpu().numpy())
+    lp_gpu = f64(res.logprob[rt])
+    print(f"[{name}] sampled rows={rows.size} max|dlogprob|={np.abs(lp_gpu - lp_ref).max():.3e}", flush=True)
+    assert np.abs(lp_gpu - lp_ref).max() <= 2e-2
+    assert float(res.logprob.max()) <= 0.0 and bool(torch.isfinite(res.logprob).all())
+    vstar_ref = orc.group_value_estimate(f64(b.rewards), b.group_ids.cpu().numpy(), b.n_groups, b.beta)
+    assert np.abs(f64(res.vstar) - vstar_ref).max() <= 1e-6
+    if name == "r1_14b":      # forced all-fail / all-pass prompts: the estimate is the reward itself
+        assert res.vstar[0].item() == 0.0 and res.vstar[1].item() == 1.0
+
+    # ---- (C) properties at full size ----------------------------------------------------------
+    lens = np.diff(off)
+    seg = _segment_sums(res.logprob.double() - b.logq.double(), b.seq_offsets)
+    Delta = f64(res.seq_logratio)
+    assert np.all(np.abs(Delta - seg) <= 3e-7 * np.maximum(lens, 1) + 1e-6 * np.abs(seg) + 1e-6)
+    gid = b.group_ids.cpu().numpy()
+    delta = b.beta * Delta - (f64(b.rewards) - vstar_ref[gid])
+    assert rel(float(res.loss.item()), float(np.sum(delta * delta))) <= 1e-5
+    if cfg.backward:
+        coeff_rows = np.empty(rows.size)
+        seq_of = np.searchsorted(off, rows, side="right") - 1
+        coeff_rows = 2.0 * b.beta * delta[seq_of]
+        g_ref = orc.grad_hidden_rows(f64(b.H[rt]), W64, b.tokens[rt].cpu().numpy(), coeff_rows,
+                                     np.arange(rows.size))
+        g_gpu = f64(res.dH[rt])
+        bound = 2e-2 * np.abs(g_ref) + 6e-3 * np.abs(g_ref).max(axis=1, keepdims=True)
+        assert np.all(np.abs(g_gpu - g_ref) <= bound), float(np.abs(g_gpu - g_ref).max())
+        assert bool(torch.isfinite(res.dW).all()) and bool(torch.isfinite(res.dH.float()).all())
+        col = res.dW.double().sum(0)
+        colabs = res.dW.double().abs().sum(0)
+        assert float((col.abs() / colabs).max()) <= 5e-3
+        # <dH, H> = <dW, W> = sum_t c_t (z_{t,y_t} - E_p z_t).  Rollouts pull in both directions
+        # (c_t changes sign with the residual), so the bound is relative to the gross per-token sum.
+        per_token = (res.dH.double() * b.H.double()).sum(1)
+        a, gross = float(per_token.sum()), float(per_token.abs().sum())
+        c = float((res.dW.double() * b.W.double()).sum())
+        print(f"[{name}] <dH,H>={a:.6e} <dW,W>={c:.6e} gross={gross:.3e}", flush=True)
+        assert abs(a - c) <= 2e-3 * gross
+    del res
+    torch.cuda.empty_cache()
+
+    # ---- (B) full parity on a slice of the same configuration ---------------------------------
+    sb = _slice_batch(b)
+    sres = oapl.loss_fwd_bwd(sb.H, sb.W, sb.tokens, sb.logq, sb.seq_offsets, sb.rewards, sb.group_ids, 1,
+                             sb.beta, backward=cfg.backward)
+    torch.cuda.synchronize()
+    assert oapl.read_device_status(sres.workspace) == 0
+    ref = orc.oapl_forward_backward(f64(sb.H), W64, sb.tokens.cpu().numpy(), f64(sb.logq),
+                                    sb.seq_offsets.cpu().numpy(), f64(sb.rewards), np.zeros(4, dtype=np.int64), 1,
+                                    sb.beta, backward=cfg.backward)
+    assert np.abs(f64(sres.logprob) - ref["logprob"]).max() <= 2e-2
+    assert rel(float(sres.loss.item()), ref["loss"]) <= 1e-3
+    print(f"[{name}] slice T={sb.T} loss_rel={rel(float(sres.loss.item()), ref['loss']):.3e}", flush=True)
+    if cfg.backward:
+        dH, dW = f64(sres.dH), f64(sres.dW)
+        gn = rel(grad_norm(dH, dW), grad_norm(ref["dH"], ref["dW"]))
+        print(f"[{name}] slice gradnorm_rel={gn:.3e}", flush=True)
+        assert gn <= 1e-3
+        for got, want in ((dH, ref["dH"]), (dW, ref["dW"])):
+            bound = 2e-2 * np.abs(want) + 6e-3 * np.abs(want).max()
+            assert np.all(np.abs(got - want) <= bound), float(np.abs(got - want).max())
