@@ -22,6 +22,7 @@ typedef TileCfg<4, 2, 2, 4, 2> Cfg;
 constexpr int64_t kPanelBf16 = 65536;  // most token rows per backward panel (bf16 path)
 constexpr int64_t kPanelF32 = 4096;    // ... (fp32 path)
 constexpr int kStatusWords = 64;       // 256-byte header
+constexpr int kNumCU = 256;            // MI355X compute units (one 128 KB-LDS workgroup each)
 
 static inline int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
 
@@ -48,11 +49,20 @@ static bool make_plan(Plan& p, int64_t T, int d, int V, int n_seq, int n_groups,
   if (dtype == OAPL_BF16) {
     const int64_t n_tiles = (T + Cfg::BN - 1) / Cfg::BN;
     const int MT = (V + Cfg::BM - 1) / Cfg::BM;
-    int64_t splits = n_tiles > 0 ? (4096 + n_tiles - 1) / n_tiles : 1;
-    const int64_t max_splits = MT / 8 > 1 ? MT / 8 : 1;  // at least ~8 vocabulary tiles per workgroup
-    if (splits > max_splits) splits = max_splits;
-    if (splits > 64) splits = 64;
-    if (splits < 1) splits = 1;
+    // Vocabulary splits of the forward kernel: one workgroup per (token tile, split), one
+    // workgroup per CU at a time.  Pick the split count that wastes the least of the last round
+    // of workgroups and of the uneven division of vocabulary tiles, with at least ~8 tiles each.
+    const int64_t max_splits = MT / 8 > 1 ? (MT / 8 < 64 ? MT / 8 : 64) : 1;
+    int64_t splits = 1;
+    double best = -1.0;
+    for (int64_t c = 1; c <= max_splits && n_tiles > 0; ++c) {
+      const int64_t wgs = n_tiles * c;
+      const double rounds = (double)wgs / kNumCU;
+      const double fill = rounds / (double)((wgs + kNumCU - 1) / kNumCU);      // occupancy of the last round
+      const double even = ((double)MT / c) / (double)((MT + c - 1) / c);       // equal work per workgroup
+      const double score = fill * even;
+      if (score > best + 1e-9) { best = score; splits = c; }
+    }
     p.n_parts = (int)splits;
     // equal panels of at most kPanelBf16 rows (a short last panel would waste a whole pass
     // of the fp32 read-add-write over dW)
