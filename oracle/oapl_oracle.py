@@ -29,14 +29,19 @@ for the small betas the paper's experiments use.  Dense contractions are
 token row is independent).  There is no tiling, no online merging and no
 reordering of the definitions.
 
+The per-token policy entropy (the training-stability diagnostic of Sec. 6.1)
+is computed from the same log-soft-max.
+
 Pins (tests/test_oracle_pins.py): brute-force soft-max on tiny vocabularies in
 50-digit arithmetic, W = 0 giving -ln V, shift and permutation invariances,
 scipy's log_softmax and logsumexp, the beta -> 0 / beta -> infinity limits of
 Eq. 2, the all-equal-rewards closed form V* = r, the binary-reward closed form,
 the pi = pi_vllm closed form of Eq. 3, the constructed minimiser of Eq. 3
-(loss 0, gradient 0), and central finite differences for every element of dH
-and dW.  No value the paper prints exists for this path (it prints no worked
-example), so full-size numbers are pinned by these properties only.
+(loss 0, gradient 0), central finite differences for every element of dH
+and dW, and for the entropy: ln V for uniform logits, 50-digit brute force,
+scipy.stats.entropy, the bounds 0 <= H <= ln V and shift invariance.  No
+value the paper prints exists for this path (it prints no worked example), so
+full-size numbers are pinned by these properties only.
 """
 from __future__ import annotations
 
@@ -88,6 +93,26 @@ def token_logprobs(H, W, tokens, rows=None, slab: int = 256):
         lp[a:a + r.size] = logp[np.arange(r.size), tokens[r]]
         lse[a:a + r.size] = l
     return lp, lse
+
+
+def token_entropy(H, W, rows=None, slab: int = 256) -> np.ndarray:
+    """Entropy of the trainer policy's next-token distribution, -sum_v p_v ln p_v, per token row.
+
+    This is the quantity whose collapse (GRPO) or stability (OAPL) the paper's training-dynamics
+    discussion tracks (Sec. 6.1).  Terms with p_v = 0 contribute 0.
+    """
+    W64 = _f64(W)
+    Hn = np.asarray(H)
+    if rows is None:
+        rows = np.arange(Hn.shape[0])
+    rows = np.asarray(rows, dtype=np.int64)
+    out = np.empty(rows.size, dtype=np.float64)
+    for a in range(0, rows.size, slab):
+        r = rows[a:a + slab]
+        logp, _ = log_softmax_rows(_f64(Hn[r]) @ W64.T)
+        p = np.exp(logp)
+        out[a:a + r.size] = -np.sum(np.where(p > 0, p * logp, 0.0), axis=1)
+    return out
 
 
 # --------------------------------------------------------------------------

@@ -67,7 +67,10 @@ static bool make_plan(Plan& p, int64_t T, int d, int V, int n_seq, int n_groups,
     // equal panels of at most kPanelBf16 rows (a short last panel would waste a whole pass
     // of the fp32 read-add-write over dW)
     const int64_t n_panels = T > 0 ? (T + kPanelBf16 - 1) / kPanelBf16 : 1;
-    p.Tp = round_up(T > 0 ? (T + n_panels - 1) / n_panels : 1, Cfg::BN);
+    // with several panels, a panel of a multiple of 4096 rows gives the dH contraction (d / 256 x
+    // Tp / 256 tiles) whole rounds of kNumCU workgroups when d is a multiple of 4096
+    p.Tp = round_up(T > 0 ? (T + n_panels - 1) / n_panels : 1, n_panels > 1 ? 4096 : Cfg::BN);
+    if (p.Tp > kPanelBf16) p.Tp = kPanelBf16;
     p.n_rt_v = MT;
     p.n_rt_d = (d + kPackRows - 1) / kPackRows;
     p.n_rt_T = n_tiles > 0 ? n_tiles : 1;

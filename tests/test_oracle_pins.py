@@ -173,6 +173,43 @@ def test_token_out_of_range_is_an_error():
         orc.token_logprobs(H, W, np.array([-1, 0]))
 
 
+# ---------------------------------------------------------------- entropy --
+
+def test_entropy_uniform_is_ln_vocab_and_bounds():
+    for V, text in _golden("ln_vocab"):
+        V = int(V)
+        H = _rng(V).normal(size=(3, 4))
+        ent = orc.token_entropy(H, np.zeros((V, 4)))
+        assert np.allclose(ent, float(text), rtol=0, atol=1e-12)
+    rng = _rng(70)
+    H, W = rng.normal(size=(20, 6)) * 3, rng.normal(size=(41, 6))
+    ent = orc.token_entropy(H, W)
+    assert np.all(ent >= 0) and np.all(ent <= math.log(41) + 1e-12)
+
+
+def test_entropy_brute_force_and_scipy():
+    import scipy.stats
+    rng = _rng(71)
+    T, d, V = 7, 3, 9
+    H, W = rng.normal(size=(T, d)) * 2, rng.normal(size=(V, d))
+    ent = orc.token_entropy(H, W, slab=2)
+    z = H @ W.T
+    assert np.allclose(ent, scipy.stats.entropy(scipy.special.softmax(z, axis=1), axis=1), atol=1e-13)
+    with mpmath.workdps(50):
+        for t in range(T):
+            e = [mpmath.exp(mpmath.mpf(x)) for x in z[t]]
+            tot = sum(e)
+            want = -sum((x / tot) * mpmath.log(x / tot) for x in e)
+            assert abs(ent[t] - float(want)) < 1e-13
+    # adding a vector to every row of W shifts all logits of a row equally: same distribution
+    assert np.allclose(orc.token_entropy(H, W + rng.normal(size=d)), ent, atol=1e-12)
+    # a nearly one-hot row has nearly zero entropy; rows= selects rows of H
+    Hp = H.copy()
+    Hp[2] *= 400
+    e2 = orc.token_entropy(Hp, W, rows=np.array([2, 0]))
+    assert e2[0] < 1e-6 and e2[1] == pytest.approx(ent[0], abs=1e-13)
+
+
 # ------------------------------------------------------- sequence log-ratio --
 
 def test_sequence_logratio_exact_on_integers_and_empty_sequences():
