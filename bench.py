@@ -56,6 +56,9 @@ def parse():
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="qwen7b", help="name in synth.CONFIGS")
+    ap.add_argument("--path", choices=["loss", "logprob", "logprob_entropy"], default="loss",
+                    help="loss: the whole hot path (default). logprob / logprob_entropy: oapl_logprob_fwd alone, "
+                         "without / with the policy-entropy output (forward scoring only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-tokens", type=int, default=2048)
     ap.add_argument("--calibration-copy", action="store_true",
@@ -121,7 +124,12 @@ def main():
     dH = torch.empty_like(batch.H) if cfg.backward else None
     dW = torch.empty((V, d), dtype=torch.float32, device=dev) if cfg.backward else None
 
+    backward = cfg.backward and args.path == "loss"
+
     def step():
+        if args.path != "loss":
+            return oapl.logprob_fwd(batch.H, batch.W, batch.tokens, want_entropy=args.path == "logprob_entropy",
+                                    workspace=ws)
         return oapl.loss_fwd_bwd(batch.H, batch.W, batch.tokens, batch.logq, batch.seq_offsets, batch.rewards,
                                  batch.group_ids, batch.n_groups, batch.beta, backward=cfg.backward,
                                  workspace=ws, dH=dH, dW=dW)
@@ -138,7 +146,7 @@ def main():
     kt = oapl.timing_read()
     oapl.timing_enable(False)
     status = oapl.read_device_status(ws)
-    loss = float(res.loss.item())
+    loss = float(res.loss.item()) if args.path == "loss" else float(res[0].sum().item())
     if args.calibration_copy:
         x = torch.ones(1 << 28, dtype=torch.float32, device=dev)
         y = torch.empty_like(x)
@@ -153,9 +161,9 @@ def main():
     ms_per_step = 1e3 * elapsed / args.steps
     tokens_per_s = T * args.steps / elapsed
     flop_unit = 2.0 * V * d                                  # one V x d contraction per token
-    n_contractions = 3 if cfg.backward else 1                # logits, dH, dW (the recompute is not counted)
+    n_contractions = 3 if backward else 1                    # logits, dH, dW (the recompute is not counted)
     alg_tflops = tokens_per_s * flop_unit * n_contractions / 1e12
-    hw_tflops = tokens_per_s * flop_unit * (4 if cfg.backward else 1) / 1e12
+    hw_tflops = tokens_per_s * flop_unit * (4 if backward else 1) / 1e12
 
     # Each dense kernel executes 2*V*d flop per token it processes; over the
     # timed steps every kernel sees every token once per step.
@@ -169,7 +177,8 @@ def main():
     roofline = None
     if dom:
         traffic = None
-        if args.workload == TRAFFIC["workload"] and sources_digest() == TRAFFIC["sources_sha256_16"]:
+        if args.path == "loss" and args.workload == TRAFFIC["workload"] \
+                and sources_digest() == TRAFFIC["sources_sha256_16"]:
             t = TRAFFIC["per_launch_bytes"].get(dom)
             traffic = None if t is None else t["read"] + t["write"]
         roofline = {"bound": "mfma", "kernel": dom, "achieved": kernels[dom]["tflops"], "peak": PEAK_BF16_TFLOPS,
@@ -177,17 +186,18 @@ def main():
                     "avg_launch_ms": kernels[dom]["avg_ms"], "launches": kernels[dom]["launches"]}
 
     out = {
-        "metric": "rollout tokens/s for OAPL logprob+loss fwd+bwd; % of bf16 MFMA peak",
+        "metric": "rollout tokens/s for OAPL logprob+loss fwd+bwd; % of bf16 MFMA peak" if args.path == "loss"
+        else f"rollout tokens/s for oapl_logprob_fwd ({args.path}); % of bf16 MFMA peak",
         "value": tokens_per_s, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": cfg.dtype, "data": "synthetic",
         "config": {"workload": f"{cfg.name}: d={d} V={V} {cfg.n_prompts} prompts x {cfg.n_rollouts} rollouts, "
-                               f"T={T} packed tokens, beta={cfg.beta}, {'fwd+bwd' if cfg.backward else 'fwd only'}"},
+                               f"T={T} packed tokens, beta={cfg.beta}, {'fwd+bwd' if backward else 'fwd only'}"},
         "algorithmic_tflops": alg_tflops, "frac_of_bf16_peak_algorithmic": alg_tflops / PEAK_BF16_TFLOPS,
         "executed_tflops": hw_tflops, "frac_of_bf16_peak_executed": hw_tflops / PEAK_BF16_TFLOPS,
-        "kernels": kernels, "roofline": roofline, "loss": loss,
+        "kernels": kernels, "roofline": roofline, "loss" if args.path == "loss" else "logprob_sum": loss,
     }
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and args.path == "loss":
         out["cpu_baseline"] = cpu_baseline(batch, args.cpu_sample_tokens)
     print(json.dumps(out))
 

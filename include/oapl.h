@@ -93,13 +93,21 @@ size_t oapl_workspace_bytes(int64_t T, int32_t d, int32_t V, int32_t n_seq,
  * The T x V logits are produced tile by tile and reduced on the fly; they are
  * never stored.
  *
+ * Optionally also the entropy of pi(. | x, y_<t), the quantity whose collapse
+ * or stability the paper's training-dynamics discussion follows (Sec. 6.1):
+ *
+ *     entropy[t] = - sum_v p_{t,v} ln p_{t,v} = lse_t - sum_v p_{t,v} z_{t,v}
+ *
+ * accumulated in the same streaming pass (one more running sum per token).
+ *
  *   tokens      [T] int32, each in [0, V)
  *   logprob_out [T] float
  *   lse_out     [T] float, or NULL if not wanted
+ *   entropy_out [T] float, or NULL if not wanted (in [0, ln V])
  */
 int32_t oapl_logprob_fwd(const void* H, const void* W, const int32_t* tokens,
                          int64_t T, int32_t d, int32_t V, int32_t dtype,
-                         float* logprob_out, float* lse_out,
+                         float* logprob_out, float* lse_out, float* entropy_out,
                          void* workspace, size_t workspace_bytes, void* stream);
 
 /*

@@ -62,7 +62,7 @@ struct TileCfg {
   static_assert(BM == kPackRows && BN == kPackRows, "tiles are one packed block tall");
   static_assert(NS >= 2 && NS <= 2, "ring size");
   static_assert(kPackRows % (8 * NW) == 0, "block rows must split over waves");
-  static_assert(RED_BYTES <= LDS_BYTES, "reduction scratch must fit");
+  static_assert(RED_BYTES + RED_BYTES / 2 <= LDS_BYTES, "reduction scratch must fit");
 };
 
 typedef __attribute__((address_space(3))) char* lds_char_ptr;
@@ -298,12 +298,13 @@ __device__ __forceinline__ void strip_tile(int L, int MT, int NTl, int& mt, int&
 // and merging a new tile by the usual rescaling rule.  The first k-block of
 // the next vocabulary tile is requested before the current tile's epilogue.
 // It writes one (m2, s) pair per token and split; a later kernel merges the
-// splits.
+// splits.  With ENT it also carries u = sum_v 2^(z * log2(e) - m2) * z, from which
+// the policy entropy follows as  lse - u / s  (one more FMA per logit).
 // ---------------------------------------------------------------------------
-template <class C>
+template <class C, bool ENT>
 __global__ void __launch_bounds__(C::NT)
 k_fwd_lse(const bf16_t* __restrict__ Wp, const bf16_t* __restrict__ Hp, int V, int64_t T, int n_kt,
-          int n_splits, float2* __restrict__ partials) {
+          int n_splits, float2* __restrict__ partials, float* __restrict__ upart) {
   extern __shared__ __attribute__((aligned(1024))) char smem_raw[];
   lds_char_ptr smem = (lds_char_ptr)smem_raw;
 
@@ -326,9 +327,9 @@ k_fwd_lse(const bf16_t* __restrict__ Wp, const bf16_t* __restrict__ Hp, int V, i
   const int wm = wave / C::WN, wn = wave % C::WN;
   const int h = lane >> 5;
 
-  float m2[C::TN], s[C::TN];
+  float m2[C::TN], s[C::TN], u[C::TN];
 #pragma unroll
-  for (int j = 0; j < C::TN; ++j) { m2[j] = kNegHuge; s[j] = 0.f; }
+  for (int j = 0; j < C::TN; ++j) { m2[j] = kNegHuge; s[j] = 0.f; u[j] = 0.f; }
 
   f32x16 acc[C::TM][C::TN];
   if (mt_begin < mt_end) {
@@ -363,12 +364,19 @@ k_fwd_lse(const bf16_t* __restrict__ Wp, const bf16_t* __restrict__ Hp, int V, i
 #pragma unroll
         for (int r = 0; r < 16; ++r) mx = fmaxf(mx, acc[i][j][r]);
       const float mnew = fmaxf(m2[j], mx * kLog2e);
-      float sum = 0.f;
+      float sum = 0.f, usum = 0.f;
 #pragma unroll
       for (int i = 0; i < C::TM; ++i)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) sum += __builtin_amdgcn_exp2f(__builtin_fmaf(acc[i][j][r], kLog2e, -mnew));
-      s[j] = s[j] * __builtin_amdgcn_exp2f(m2[j] - mnew) + sum;
+        for (int r = 0; r < 16; ++r) {
+          const float e = __builtin_amdgcn_exp2f(__builtin_fmaf(acc[i][j][r], kLog2e, -mnew));
+          sum += e;
+          // masked rows hold -inf with e = 0: keep their product out (0 * inf)
+          if (ENT) usum = __builtin_fmaf(e, e > 0.f ? acc[i][j][r] : 0.f, usum);
+        }
+      const float scale = __builtin_amdgcn_exp2f(m2[j] - mnew);
+      s[j] = s[j] * scale + sum;
+      if (ENT) u[j] = u[j] * scale + usum;
       m2[j] = mnew;
     }
   }
@@ -378,29 +386,38 @@ k_fwd_lse(const bf16_t* __restrict__ Wp, const bf16_t* __restrict__ Hp, int V, i
   for (int j = 0; j < C::TN; ++j) {
     const float mo = __shfl_xor(m2[j], 32, 64), so = __shfl_xor(s[j], 32, 64);
     const float M = fmaxf(m2[j], mo);
-    s[j] = s[j] * __builtin_amdgcn_exp2f(m2[j] - M) + so * __builtin_amdgcn_exp2f(mo - M);
+    const float fa = __builtin_amdgcn_exp2f(m2[j] - M), fb = __builtin_amdgcn_exp2f(mo - M);
+    s[j] = s[j] * fa + so * fb;
+    if (ENT) u[j] = u[j] * fa + __shfl_xor(u[j], 32, 64) * fb;
     m2[j] = M;
   }
   // ... then the WM waves stacked along the vocabulary, through LDS.
   typedef float f32x2 __attribute__((ext_vector_type(2)));
   __attribute__((address_space(3))) f32x2* red = (__attribute__((address_space(3))) f32x2*)smem;
+  __attribute__((address_space(3))) float* red_u = (__attribute__((address_space(3))) float*)(smem + C::RED_BYTES);
   if (h == 0) {
 #pragma unroll
-    for (int j = 0; j < C::TN; ++j)
+    for (int j = 0; j < C::TN; ++j) {
       red[wm * C::BN + wn * C::TN * 32 + j * 32 + lane] = f32x2{m2[j], s[j]};
+      if (ENT) red_u[wm * C::BN + wn * C::TN * 32 + j * 32 + lane] = u[j];
+    }
   }
   __syncthreads();
   for (int n_l = threadIdx.x; n_l < C::BN; n_l += C::NT) {
     if (n0 + n_l < T) {
       f32x2 a = red[n_l];
+      float ua = ENT ? red_u[n_l] : 0.f;
 #pragma unroll
       for (int w = 1; w < C::WM; ++w) {
         const f32x2 b = red[w * C::BN + n_l];
         const float M = fmaxf(a.x, b.x);
-        a.y = a.y * __builtin_amdgcn_exp2f(a.x - M) + b.y * __builtin_amdgcn_exp2f(b.x - M);
+        const float fa = __builtin_amdgcn_exp2f(a.x - M), fb = __builtin_amdgcn_exp2f(b.x - M);
+        a.y = a.y * fa + b.y * fb;
+        if (ENT) ua = ua * fa + red_u[w * C::BN + n_l] * fb;
         a.x = M;
       }
       partials[(int64_t)split * T + n0 + n_l] = make_float2(a.x, a.y);
+      if (ENT) upart[(int64_t)split * T + n0 + n_l] = ua;
     }
   }
 }

@@ -53,6 +53,7 @@ k_gemm_f32(F32Operand A, F32Operand B, int64_t M, int64_t N, int64_t K, Epi epi)
 struct EpiLseF32 {
   float2* parts;
   int64_t T;
+  float* upart;  // optional third partial u = sum_v exp(z - m) * z (for the entropy), or nullptr
   __device__ void operator()(float (&acc)[4][4], int64_t m, int64_t n, int64_t M, int64_t N) const {
     const int64_t part = n >> 6;
 #pragma unroll
@@ -66,12 +67,19 @@ struct EpiLseF32 {
 #pragma unroll
       for (int o = 8; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o, 64));
       const float ref = fmaxf(mx, kNegHuge);
-      float s = 0.f;
+      float s = 0.f, u = 0.f;
 #pragma unroll
-      for (int j = 0; j < 4; ++j) s += expf(acc[i][j] - ref);
+      for (int j = 0; j < 4; ++j) {
+        const float e = expf(acc[i][j] - ref);
+        s += e;
+        u += e > 0.f ? e * acc[i][j] : 0.f;
+      }
 #pragma unroll
-      for (int o = 8; o > 0; o >>= 1) s += __shfl_xor(s, o, 64);
-      if ((threadIdx.x & 15) == 0 && m + i < M) parts[part * T + m + i] = make_float2(ref, s);
+      for (int o = 8; o > 0; o >>= 1) { s += __shfl_xor(s, o, 64); u += __shfl_xor(u, o, 64); }
+      if ((threadIdx.x & 15) == 0 && m + i < M) {
+        parts[part * T + m + i] = make_float2(ref, s);
+        if (upart) upart[part * T + m + i] = u;
+      }
     }
   }
 };

@@ -35,7 +35,7 @@ struct Plan {
   // packed-operand geometry (bf16 path): row tiles and k-blocks (strip pitches)
   int n_rt_v = 0, n_rt_d = 0, n_kt_d = 0, n_kt_v = 0, n_kt_g = 0, n_kt_t = 0;
   int64_t n_rt_T = 0;
-  size_t off_status = 0, off_partials = 0, off_zy = 0, off_lse2 = 0, off_diff = 0, off_coef = 0, off_delta = 0,
+  size_t off_status = 0, off_partials = 0, off_upart = 0, off_zy = 0, off_lse2 = 0, off_diff = 0, off_coef = 0, off_delta = 0,
          off_cseq = 0, off_vstar = 0, off_omp = 0, off_inv = 0, off_Wp = 0, off_Hp = 0, off_WTp = 0, off_HTp = 0,
          off_G = 0, off_GT = 0, total = 0;
 };
@@ -87,6 +87,7 @@ static bool make_plan(Plan& p, int64_t T, int d, int V, int n_seq, int n_groups,
   const size_t Tn = (size_t)(T > 0 ? T : 1);
   p.off_status = take(kStatusWords * 4);
   p.off_partials = take(Tn * (size_t)p.n_parts * 8);
+  p.off_upart = take(Tn * (size_t)p.n_parts * 4);
   p.off_zy = take(Tn * 4);
   p.off_lse2 = take(Tn * 4);
   p.off_diff = take(Tn * 8);
@@ -161,7 +162,8 @@ static bool prepare_kernels() {
   static std::once_flag once;
   static bool ok = false;
   std::call_once(once, [] {
-    ok = allow_big_lds(k_fwd_lse<Cfg>, Cfg::LDS_BYTES) && allow_big_lds(k_bwd_dz<Cfg>, Cfg::LDS_BYTES) &&
+    ok = allow_big_lds(k_fwd_lse<Cfg, false>, Cfg::LDS_BYTES) && allow_big_lds(k_fwd_lse<Cfg, true>, Cfg::LDS_BYTES) &&
+         allow_big_lds(k_bwd_dz<Cfg>, Cfg::LDS_BYTES) &&
          allow_big_lds(k_bwd_dh<Cfg>, Cfg::LDS_BYTES) && allow_big_lds(k_bwd_dw<Cfg>, Cfg::LDS_BYTES);
   });
   return ok;
@@ -171,9 +173,11 @@ static bool prepare_kernels() {
 // finish.  Writes logprob / lse if wanted, and (for the loss) lse in the
 // kernels' exponent domain plus logprob - logq in double.
 static int forward_scores(const Plan& p, const void* H, const void* W, const int32_t* tokens, const float* logq,
-                          float* logprob_out, float* lse_out, char* ws, bool keep_for_loss, hipStream_t st) {
+                          float* logprob_out, float* lse_out, float* entropy_out, char* ws, bool keep_for_loss,
+                          hipStream_t st) {
   int* status = (int*)(ws + p.off_status);
   float2* partials = (float2*)(ws + p.off_partials);
+  float* upart = entropy_out ? (float*)(ws + p.off_upart) : nullptr;
   float* zy = (float*)(ws + p.off_zy);
   float* lse2 = keep_for_loss ? (float*)(ws + p.off_lse2) : nullptr;
   double* diff = keep_for_loss ? (double*)(ws + p.off_diff) : nullptr;
@@ -200,12 +204,16 @@ static int forward_scores(const Plan& p, const void* H, const void* W, const int
     const int64_t total = n_tiles * p.n_parts;
     {
       ScopedKernelTimer tm(kFwdLse, st);
-      k_fwd_lse<Cfg><<<(unsigned)round_up(total, 8), Cfg::NT, Cfg::LDS_BYTES, st>>>(Wp, Hp, p.V, T, p.n_kt_d,
-                                                                                    p.n_parts, partials);
+      if (entropy_out)
+        k_fwd_lse<Cfg, true><<<(unsigned)round_up(total, 8), Cfg::NT, Cfg::LDS_BYTES, st>>>(Wp, Hp, p.V, T, p.n_kt_d,
+                                                                                            p.n_parts, partials, upart);
+      else
+        k_fwd_lse<Cfg, false><<<(unsigned)round_up(total, 8), Cfg::NT, Cfg::LDS_BYTES, st>>>(
+            Wp, Hp, p.V, T, p.n_kt_d, p.n_parts, partials, nullptr);
     }
     OAPL_LAUNCH_CHECK();
     k_lse_finish<true><<<grid1d(T, 256), 256, 0, st>>>(partials, p.n_parts, T, zy, logq, logprob_out, lse_out, lse2,
-                                                       diff, omp, inv);
+                                                       diff, omp, inv, upart, entropy_out);
     OAPL_LAUNCH_CHECK();
   } else {
     k_gather_logit<float, double><<<grid1d(T, 4), 256, 0, st>>>((const float*)H, (const float*)W, tokens, T, p.d, p.V,
@@ -213,10 +221,10 @@ static int forward_scores(const Plan& p, const void* H, const void* W, const int
     OAPL_LAUNCH_CHECK();
     F32Operand A{(const float*)H, p.d, 1}, B{(const float*)W, p.d, 1};
     dim3 grid(grid1d(p.V, 64), grid1d(T, 64));
-    k_gemm_f32<<<grid, 256, 0, st>>>(A, B, T, (int64_t)p.V, (int64_t)p.d, EpiLseF32{partials, T});
+    k_gemm_f32<<<grid, 256, 0, st>>>(A, B, T, (int64_t)p.V, (int64_t)p.d, EpiLseF32{partials, T, upart});
     OAPL_LAUNCH_CHECK();
     k_lse_finish<false><<<grid1d(T, 256), 256, 0, st>>>(partials, p.n_parts, T, zy, logq, logprob_out, lse_out, lse2,
-                                                        diff, omp, inv);
+                                                        diff, omp, inv, upart, entropy_out);
     OAPL_LAUNCH_CHECK();
   }
   return OAPL_OK;
@@ -329,7 +337,7 @@ static int loss_impl(const void* H, const void* W, const int32_t* tokens, const 
 
   hipStream_t st = (hipStream_t)stream;
   char* ws = (char*)workspace;
-  if (int rc = forward_scores(p, H, W, tokens, logq, logprob_out, nullptr, ws, true, st)) return rc;
+  if (int rc = forward_scores(p, H, W, tokens, logq, logprob_out, nullptr, nullptr, ws, true, st)) return rc;
 
   double* Delta = (double*)(ws + p.off_delta);
   float* cseq = (float*)(ws + p.off_cseq);
@@ -387,15 +395,16 @@ size_t oapl_workspace_bytes(int64_t T, int32_t d, int32_t V, int32_t n_seq, int3
 }
 
 int32_t oapl_logprob_fwd(const void* H, const void* W, const int32_t* tokens, int64_t T, int32_t d, int32_t V,
-                         int32_t dtype, float* logprob_out, float* lse_out, void* workspace, size_t workspace_bytes,
-                         void* stream) {
+                         int32_t dtype, float* logprob_out, float* lse_out, float* entropy_out, void* workspace,
+                         size_t workspace_bytes, void* stream) {
   if (dtype != OAPL_F32 && dtype != OAPL_BF16) return OAPL_ERR_DTYPE;
   Plan p;
   if (!make_plan(p, T, d, V, 0, 1, dtype, false)) return OAPL_ERR_SHAPE;
   if (!W) return OAPL_ERR_NULL;
   if (T > 0 && (!H || !tokens || !logprob_out)) return OAPL_ERR_NULL;
   if (int rc = check_workspace(workspace, workspace_bytes, p.total)) return rc;
-  return forward_scores(p, H, W, tokens, nullptr, logprob_out, lse_out, (char*)workspace, false, (hipStream_t)stream);
+  return forward_scores(p, H, W, tokens, nullptr, logprob_out, lse_out, entropy_out, (char*)workspace, false,
+                        (hipStream_t)stream);
 }
 
 int32_t oapl_loss_fwd_bwd(const void* H, const void* W, const int32_t* tokens, const float* logq,

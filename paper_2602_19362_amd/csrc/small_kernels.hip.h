@@ -46,7 +46,9 @@ k_gather_logit(const T* __restrict__ H, const T* __restrict__ W, const int32_t* 
 }
 
 // Merges the per-split soft-max partials of each token and finishes
-//   lse_t = ln sum_v exp(z_tv),   logprob_t = min(z_{t,y_t} - lse_t, 0).
+//   lse_t = ln sum_v exp(z_tv),   logprob_t = min(z_{t,y_t} - lse_t, 0),
+// and, when asked for, the entropy of the token's distribution from the extra
+// partial u = sum b^(zeta - m) * z.
 // A partial is (m, s) with s = sum b^(zeta - m): LOG2 = true means zeta =
 // z * log2(e), b = 2 (the MFMA kernel's epilogue); false means zeta = z, b = e.
 // Everything after the fp32 partials is done in double.
@@ -55,22 +57,26 @@ __global__ void __launch_bounds__(256)
 k_lse_finish(const float2* __restrict__ partials, int n_parts, int64_t Ttok, const float* __restrict__ zy,
              const float* __restrict__ logq, float* __restrict__ logprob_out, float* __restrict__ lse_out,
              float* __restrict__ lse2_ws, double* __restrict__ diff_ws, float* __restrict__ omp_ws,
-             float* __restrict__ inv_omp_ws) {
+             float* __restrict__ inv_omp_ws, const float* __restrict__ upart, float* __restrict__ entropy_out) {
   const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (t >= Ttok) return;
   float M = kNegHuge;
   for (int p = 0; p < n_parts; ++p) M = fmaxf(M, partials[(int64_t)p * Ttok + t].x);
-  double S = 0.0;
+  double S = 0.0, U = 0.0;
   for (int p = 0; p < n_parts; ++p) {
     const float2 a = partials[(int64_t)p * Ttok + t];
     const double e = (double)a.x - (double)M;
-    S += (double)a.y * (LOG2 ? exp2(e) : exp(e));
+    const double f = LOG2 ? exp2(e) : exp(e);
+    S += (double)a.y * f;
+    if (entropy_out) U += (double)upart[(int64_t)p * Ttok + t] * f;
   }
   const double lse = LOG2 ? ((double)M + log2(S)) * kLn2 : (double)M + log(S);
   double lp = (double)zy[t] - lse;   // NaN if the token was out of range
   if (lp > 0.0) lp = 0.0;            // the gathered logit is rounded separately from the sum
   if (logprob_out) logprob_out[t] = (float)lp;
   if (lse_out) lse_out[t] = (float)lse;
+  // policy entropy  -sum_v p_v ln p_v = lse - sum_v p_v z_v  with  sum_v p_v z_v = U / S  (>= 0 up to rounding)
+  if (entropy_out) entropy_out[t] = (float)fmax(lse - U / S, 0.0);
   // the backward kernels want lse in the domain their exponentials work in
   if (lse2_ws) lse2_ws[t] = (float)(LOG2 ? lse * (double)1.4426950408889634074 : lse);
   if (diff_ws) diff_ws[t] = lp - (double)logq[t];

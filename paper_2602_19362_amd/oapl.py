@@ -31,7 +31,8 @@ _SIGNATURES = {
     "oapl_workspace_bytes": (_c.c_size_t, [_c.c_int64, _c.c_int32, _c.c_int32, _c.c_int32, _c.c_int32, _c.c_int32,
                                            _c.c_int32]),
     "oapl_logprob_fwd": (_c.c_int32, [_c.c_void_p, _c.c_void_p, _c.c_void_p, _c.c_int64, _c.c_int32, _c.c_int32,
-                                      _c.c_int32, _c.c_void_p, _c.c_void_p, _c.c_void_p, _c.c_size_t, _c.c_void_p]),
+                                      _c.c_int32, _c.c_void_p, _c.c_void_p, _c.c_void_p, _c.c_void_p, _c.c_size_t,
+                                      _c.c_void_p]),
     "oapl_loss_fwd_bwd": (_c.c_int32, [_c.c_void_p] * 7 + [_c.c_int64] + [_c.c_int32] * 5 + [_c.c_float] * 2 +
                           [_c.c_void_p] * 7 + [_c.c_size_t, _c.c_void_p]),
     "oapl_loss_fwd_bwd_two_beta": (_c.c_int32, [_c.c_void_p] * 7 + [_c.c_int64] + [_c.c_int32] * 5 + [_c.c_float] * 3 +
@@ -124,8 +125,11 @@ def read_device_status(workspace: torch.Tensor) -> int:
 
 
 def logprob_fwd(H: torch.Tensor, W: torch.Tensor, tokens: torch.Tensor, *, want_lse: bool = False,
-                workspace: Optional[torch.Tensor] = None):
-    """oapl_logprob_fwd: per-token log-probs of the sampled tokens (and lse)."""
+                want_entropy: bool = False, workspace: Optional[torch.Tensor] = None):
+    """oapl_logprob_fwd: per-token log-probs of the sampled tokens (and lse, and the policy entropy).
+
+    Returns (logprob, [lse], [entropy], workspace) with the optional items present when asked for.
+    """
     L = lib()
     dt = _dtype_code(H)
     T, d = H.shape
@@ -139,12 +143,14 @@ def logprob_fwd(H: torch.Tensor, W: torch.Tensor, tokens: torch.Tensor, *, want_
     ws = _workspace(nbytes, dev, workspace)
     logprob = torch.empty(T, dtype=torch.float32, device=dev)
     lse = torch.empty(T, dtype=torch.float32, device=dev) if want_lse else None
+    ent = torch.empty(T, dtype=torch.float32, device=dev) if want_entropy else None
     rc = L.oapl_logprob_fwd(_dev(H, H.dtype, "H", dev), _dev(W, H.dtype, "W", dev),
                             _dev(tokens, torch.int32, "tokens", dev), T, d, V, dt, logprob.data_ptr(),
-                            lse.data_ptr() if want_lse else None, ws.data_ptr(), ws.numel(), _stream(dev))
+                            lse.data_ptr() if want_lse else None, ent.data_ptr() if want_entropy else None,
+                            ws.data_ptr(), ws.numel(), _stream(dev))
     if rc != 0:
         raise OaplError(rc, "oapl_logprob_fwd")
-    return (logprob, lse, ws) if want_lse else (logprob, ws)
+    return tuple(x for x in (logprob, lse, ent) if x is not None) + (ws,)
 
 
 class LossResult(NamedTuple):

@@ -59,13 +59,13 @@ def test_host_side_errors_return_before_any_launch():
     L = oapl.lib()
     one = ctypes.c_void_p(256)          # never dereferenced: the checks below fail first
     # dtype / shape / null
-    assert L.oapl_logprob_fwd(one, one, one, 4, 8, 8, 7, one, None, one, 1 << 20, None) == 3
-    assert L.oapl_logprob_fwd(one, one, one, 4, 0, 8, 0, one, None, one, 1 << 20, None) == 2
-    assert L.oapl_logprob_fwd(None, one, one, 4, 8, 8, 0, one, None, one, 1 << 20, None) == 1
+    assert L.oapl_logprob_fwd(one, one, one, 4, 8, 8, 7, one, None, None, one, 1 << 20, None) == 3
+    assert L.oapl_logprob_fwd(one, one, one, 4, 0, 8, 0, one, None, None, one, 1 << 20, None) == 2
+    assert L.oapl_logprob_fwd(None, one, one, 4, 8, 8, 0, one, None, None, one, 1 << 20, None) == 1
     # workspace: null, misaligned, too small
-    assert L.oapl_logprob_fwd(one, one, one, 4, 8, 8, 0, one, None, None, 1 << 20, None) == 7
-    assert L.oapl_logprob_fwd(one, one, one, 4, 8, 8, 0, one, None, ctypes.c_void_p(260), 1 << 20, None) == 7
-    assert L.oapl_logprob_fwd(one, one, one, 4, 8, 8, 0, one, None, one, 16, None) == 7
+    assert L.oapl_logprob_fwd(one, one, one, 4, 8, 8, 0, one, None, None, None, 1 << 20, None) == 7
+    assert L.oapl_logprob_fwd(one, one, one, 4, 8, 8, 0, one, None, None, ctypes.c_void_p(260), 1 << 20, None) == 7
+    assert L.oapl_logprob_fwd(one, one, one, 4, 8, 8, 0, one, None, None, one, 16, None) == 7
 
     def loss(beta=1.0, scale=1.0, dH=one, dW=one, dtype=0, n_groups=1, ws_bytes=1 << 24):
         return L.oapl_loss_fwd_bwd(one, one, one, one, one, one, one, 4, 8, 8, 2, n_groups, dtype,

@@ -89,6 +89,15 @@ def test_full_size_configuration(name):
     print(f"[{name}] sampled rows={rows.size} max|dlogprob|={np.abs(lp_gpu - lp_ref).max():.3e}", flush=True)
     assert np.abs(lp_gpu - lp_ref).max() <= 2e-2
     assert float(res.logprob.max()) <= 0.0 and bool(torch.isfinite(res.logprob).all())
+    if name == "qwen1p7b_fwd":     # the forward-only configuration also exercises the entropy output at full size
+        lp2, ent, ws2 = oapl.logprob_fwd(b.H, b.W, b.tokens, want_entropy=True)
+        torch.cuda.synchronize()
+        assert oapl.read_device_status(ws2) == 0 and torch.equal(lp2, res.logprob)
+        ent_ref = orc.token_entropy(f64(b.H[rt]), W64)
+        print(f"[{name}] max|dentropy|={np.abs(f64(ent[rt]) - ent_ref).max():.3e}", flush=True)
+        assert np.abs(f64(ent[rt]) - ent_ref).max() <= 2e-2
+        assert float(ent.min()) >= 0.0 and float(ent.max()) <= np.log(V) + 1e-4
+        del lp2, ent, ws2
     vstar_ref = orc.group_value_estimate(f64(b.rewards), b.group_ids.cpu().numpy(), b.n_groups, b.beta)
     assert np.abs(f64(res.vstar) - vstar_ref).max() <= 1e-6
     if name == "r1_14b":      # forced all-fail / all-pass prompts: the estimate is the reward itself

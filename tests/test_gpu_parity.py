@@ -154,6 +154,32 @@ def test_logprob_fwd_entry_point_and_lse():
     assert np.abs(f64(lse) - ref["lse"]).max() <= 1e-5
 
 
+@pytest.mark.parametrize("dtype,d,V,T,tol", [("f32", 40, 777, 130, 2e-5), ("bf16", 128, 3000, 700, 2e-2),
+                                             ("bf16", 320, 1000, 300, 2e-2)])
+def test_policy_entropy_in_the_streaming_pass(dtype, d, V, T, tol):
+    """entropy[t] = -sum_v p ln p, accumulated beside the log-sum-exp; oracle: the definition."""
+    from oracle import oapl_oracle as orc
+    b = _custom_batch(dtype, d=d, V=V, lens=[T], n_groups=1, seed=20, beta=1.0)
+    lp, ent, ws = oapl.logprob_fwd(b.H, b.W, b.tokens, want_entropy=True)
+    torch.cuda.synchronize()
+    assert oapl.read_device_status(ws) == 0
+    ref = orc.token_entropy(f64(b.H), f64(b.W))
+    got = f64(ent)
+    assert np.abs(got - ref).max() <= tol
+    assert np.all(got >= 0) and np.all(got <= np.log(V) + 1e-4)
+    # asking for the entropy must not change the log-probs
+    lp0, _ = oapl.logprob_fwd(b.H, b.W, b.tokens)
+    assert torch.equal(lp, lp0)
+    # peaked distributions (hidden states x 30): entropy near zero, still accurate and non-negative
+    Hp = (b.H.float() * 30).to(b.H.dtype)
+    _, entp, _ = oapl.logprob_fwd(Hp, b.W, b.tokens, want_entropy=True)
+    refp = orc.token_entropy(f64(Hp), f64(b.W))
+    assert np.abs(f64(entp) - refp).max() <= 5 * tol and float(entp.min()) >= 0.0
+    # uniform distribution (zero weights): exactly ln V up to fp32 rounding
+    _, entu, _ = oapl.logprob_fwd(b.H, torch.zeros_like(b.W), b.tokens, want_entropy=True)
+    assert np.abs(f64(entu) - np.log(V)).max() <= 2e-6 * np.log(V) + 1e-6
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_integer_inputs_make_the_gather_exact(dtype):
     """Integer H, W: every logit is an exact integer in any summation order, so
