@@ -71,8 +71,9 @@ const char* oapl_status_string(int32_t status);
 
 /*
  * Shape limits: T >= 0 (T == 0 is legal and yields loss = sum of squared
- * advantages), 1 <= d, 1 <= V, d and V < 2^31, 0 <= n_seq, 1 <= n_groups.
- * OAPL_BF16 additionally needs d to be a multiple of 8 (16-byte rows).
+ * advantages), 1 <= d <= 2^21, 1 <= V <= 2^21, 0 <= n_seq, 1 <= n_groups.
+ * OAPL_BF16 additionally needs d to be a multiple of 8 (16-byte rows) and
+ * T <= 65535 * 256.  Anything else is OAPL_ERR_SHAPE.
  */
 
 /* Bytes of workspace the two calls below need for these sizes (host call, no

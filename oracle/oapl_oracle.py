@@ -30,7 +30,11 @@ token row is independent).  There is no tiling, no online merging and no
 reordering of the definitions.
 
 The per-token policy entropy (the training-stability diagnostic of Sec. 6.1)
-is computed from the same log-soft-max.
+is computed from the same log-soft-max.  The sampling step of Alg. 1 (draw
+y_t from softmax(z_t / temperature)) is stated as a Gumbel-max draw over a
+counter-based generator (Philox-4x32-10) so that a GPU kernel can reproduce
+the same draws; it is pinned by the generator's published known-answer
+vectors and by the draw frequencies matching the soft-max.
 
 Pins (tests/test_oracle_pins.py): brute-force soft-max on tiny vocabularies in
 50-digit arithmetic, W = 0 giving -ln V, shift and permutation invariances,
@@ -113,6 +117,71 @@ def token_entropy(H, W, rows=None, slab: int = 256) -> np.ndarray:
         p = np.exp(logp)
         out[a:a + r.size] = -np.sum(np.where(p > 0, p * logp, 0.0), axis=1)
     return out
+
+
+# --------------------------------------------------------------------------
+# Sampling step of Alg. 1: y_t ~ softmax(z_t / temperature) by the Gumbel-max construction
+# --------------------------------------------------------------------------
+
+_PHILOX_M0, _PHILOX_M1 = 0xD2511F53, 0xCD9E8D57
+_PHILOX_W0, _PHILOX_W1 = 0x9E3779B9, 0xBB67AE85
+
+
+def philox4x32_10(counter, key):
+    """Philox-4x32 with 10 rounds (Salmon, Moraes, Dror, Shaw: "Parallel random numbers: as easy
+    as 1, 2, 3", SC'11), vectorised: counter [..., 4] and key [..., 2] uint32 -> [..., 4] uint32."""
+    c = [np.asarray(counter)[..., i].astype(np.uint64) for i in range(4)]
+    k0 = np.asarray(key)[..., 0].astype(np.uint64)
+    k1 = np.asarray(key)[..., 1].astype(np.uint64)
+    mask = np.uint64(0xFFFFFFFF)
+    for _ in range(10):
+        p0 = np.uint64(_PHILOX_M0) * c[0]
+        p1 = np.uint64(_PHILOX_M1) * c[2]
+        c = [(p1 >> np.uint64(32)) ^ c[1] ^ k0, p1 & mask, (p0 >> np.uint64(32)) ^ c[3] ^ k1, p0 & mask]
+        k0 = (k0 + np.uint64(_PHILOX_W0)) & mask
+        k1 = (k1 + np.uint64(_PHILOX_W1)) & mask
+    return np.stack(c, axis=-1).astype(np.uint32)
+
+
+def gumbel_noise(rows, V: int, seed: int) -> np.ndarray:
+    """g[t, v] = -ln(-ln u[t, v]) for the given token rows, all v in [0, V).
+
+    u comes from Philox-4x32-10 with key (seed low word, seed high word) and counter
+    (v // 4, t low word, t high word, 0); output word v % 4 gives x, and
+    u = ((x >> 9) + 1/2) * 2^-23, which lies strictly inside (0, 1) and is exact in binary32.
+    """
+    rows = np.asarray(rows, dtype=np.int64)
+    nb = (V + 3) // 4
+    ctr = np.zeros((rows.size, nb, 4), dtype=np.uint32)
+    ctr[:, :, 0] = np.arange(nb, dtype=np.uint32)[None, :]
+    ctr[:, :, 1] = (rows & 0xFFFFFFFF).astype(np.uint32)[:, None]
+    ctr[:, :, 2] = (rows >> 32).astype(np.uint32)[:, None]
+    key = np.array([seed & 0xFFFFFFFF, (seed >> 32) & 0xFFFFFFFF], dtype=np.uint32)
+    x = philox4x32_10(ctr, np.broadcast_to(key, ctr.shape[:-1] + (2,))).reshape(rows.size, nb * 4)[:, :V]
+    u = ((x >> np.uint32(9)).astype(np.float64) + 0.5) * 2.0 ** -23
+    return -np.log(-np.log(u))
+
+
+def sample_tokens(H, W, temperature: float, seed: int, rows=None, slab: int = 128):
+    """One draw per token row from softmax(z_t / temperature): argmax_v (z_tv / temperature + g_tv)
+    (ties to the smallest v).  Returns (tokens, scores) where scores[t] is the winning perturbed logit.
+    """
+    if not temperature > 0:
+        raise ValueError("temperature must be positive")
+    W64 = _f64(W)
+    Hn = np.asarray(H)
+    V = W64.shape[0]
+    if rows is None:
+        rows = np.arange(Hn.shape[0])
+    rows = np.asarray(rows, dtype=np.int64)
+    tok = np.empty(rows.size, dtype=np.int64)
+    best = np.empty(rows.size, dtype=np.float64)
+    for a in range(0, rows.size, slab):
+        r = rows[a:a + slab]
+        score = (_f64(Hn[r]) @ W64.T) / float(temperature) + gumbel_noise(r, V, seed)
+        tok[a:a + r.size] = np.argmax(score, axis=1)
+        best[a:a + r.size] = score[np.arange(r.size), tok[a:a + r.size]]
+    return tok, best
 
 
 # --------------------------------------------------------------------------

@@ -44,7 +44,10 @@ static bool make_plan(Plan& p, int64_t T, int d, int V, int n_seq, int n_groups,
   if (T < 0 || d < 1 || V < 1 || n_seq < 0 || n_groups < 1) return false;
   if (dtype != OAPL_F32 && dtype != OAPL_BF16) return false;
   if (dtype == OAPL_BF16 && (d % 8) != 0) return false;
-  if ((int64_t)d > (1 << 22) || (int64_t)V > (1ll << 30)) return false;
+  // a packed row-tile strip (K / 64 blocks of 32 KiB) must stay below 2 GiB for 32-bit buffer offsets,
+  // and the packing kernels index token tiles with gridDim.y
+  if ((int64_t)d > (1 << 21) || (int64_t)V > (1 << 21)) return false;
+  if (dtype == OAPL_BF16 && T > (int64_t)65535 * 256) return false;
   p.T = T; p.d = d; p.V = V; p.n_seq = n_seq; p.n_groups = n_groups; p.dtype = dtype; p.bwd = bwd;
   if (dtype == OAPL_BF16) {
     const int64_t n_tiles = (T + Cfg::BN - 1) / Cfg::BN;

@@ -210,6 +210,65 @@ def test_entropy_brute_force_and_scipy():
     assert e2[0] < 1e-6 and e2[1] == pytest.approx(ent[0], abs=1e-13)
 
 
+# ---------------------------------------------------------------- sampling --
+
+def test_philox_known_answers():
+    """Known-answer vectors published with the generator (Random123 kat_vectors, philox4x32 10)."""
+    kat = [
+        ((0, 0, 0, 0), (0, 0), (0x6627e8d5, 0xe169c58d, 0xbc57ac4c, 0x9b00dbd8)),
+        ((0xffffffff,) * 4, (0xffffffff,) * 2, (0x408f276d, 0x41c83b0e, 0xa20bc7c6, 0x6d5451fd)),
+        ((0x243f6a88, 0x85a308d3, 0x13198a2e, 0x03707344), (0xa4093822, 0x299f31d0),
+         (0xd16cfe09, 0x94fdcceb, 0x5001e420, 0x24126ea1)),
+    ]
+    for ctr, key, want in kat:
+        got = orc.philox4x32_10(np.array(ctr, dtype=np.uint32), np.array(key, dtype=np.uint32))
+        assert tuple(int(x) for x in got) == want
+    # vectorised call = element-wise call
+    c = np.array([k[0] for k in kat], dtype=np.uint32)
+    k = np.array([k[1] for k in kat], dtype=np.uint32)
+    assert np.array_equal(orc.philox4x32_10(c, k), np.array([k_[2] for k_ in kat], dtype=np.uint32))
+
+
+def test_gumbel_noise_layout_and_range():
+    g = orc.gumbel_noise(np.array([0, 5, 2 ** 33 + 1]), 10, seed=(7 << 32) | 3)
+    assert g.shape == (3, 10) and np.all(np.isfinite(g))
+    # word v % 4 of the block with counter (v // 4, t_lo, t_hi, 0) and key (seed_lo, seed_hi)
+    x = orc.philox4x32_10(np.array([2, 1, 2, 0], dtype=np.uint32), np.array([3, 7], dtype=np.uint32))
+    u = ((int(x[1]) >> 9) + 0.5) * 2.0 ** -23
+    assert g[2, 9] == -np.log(-np.log(u))
+    # different rows, seeds and columns give different noise; the same arguments the same noise
+    assert not np.array_equal(g[0], g[1])
+    assert np.array_equal(orc.gumbel_noise(np.array([5]), 10, seed=(7 << 32) | 3)[0], g[1])
+    assert not np.array_equal(orc.gumbel_noise(np.array([5]), 10, seed=4)[0], g[1])
+    # standard Gumbel: mean = Euler's constant, variance = pi^2 / 6
+    big = orc.gumbel_noise(np.arange(64), 4096, seed=11).ravel()
+    assert abs(big.mean() - 0.5772156649) < 0.01 and abs(big.var() - np.pi ** 2 / 6) < 0.03
+
+
+def test_sampled_tokens_follow_the_softmax():
+    """Frequencies over many rows with identical hidden state match softmax(z / temperature)."""
+    rng = _rng(80)
+    d, V, n = 4, 6, 40000
+    h = rng.normal(size=d)
+    W = rng.normal(size=(V, d))
+    H = np.tile(h, (n, 1))
+    for temp in (1.0, 0.6):
+        tok, best = orc.sample_tokens(H, W, temp, seed=123)
+        p = scipy.special.softmax((W @ h) / temp)
+        freq = np.bincount(tok, minlength=V) / n
+        assert np.abs(freq - p).max() < 4 * np.sqrt(p.max() / n) + 1e-3
+        # the reported score is the winner's perturbed logit, and it is the row maximum
+        g = orc.gumbel_noise(np.arange(3), V, 123)
+        s3 = (W @ h) / temp + g
+        assert np.allclose(best[:3], s3.max(axis=1)) and np.array_equal(tok[:3], s3.argmax(axis=1))
+    # rows= selects token rows: the draw depends on the row index, not on its position in the call
+    t2, _ = orc.sample_tokens(H, W, 1.0, seed=123, rows=np.array([17, 3]))
+    t0, _ = orc.sample_tokens(H, W, 1.0, seed=123)
+    assert t2.tolist() == [t0[17], t0[3]]
+    with pytest.raises(ValueError):
+        orc.sample_tokens(H, W, 0.0, seed=1)
+
+
 # ------------------------------------------------------- sequence log-ratio --
 
 def test_sequence_logratio_exact_on_integers_and_empty_sequences():
