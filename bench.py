@@ -56,9 +56,10 @@ def parse():
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="qwen7b", help="name in synth.CONFIGS")
-    ap.add_argument("--path", choices=["loss", "logprob", "logprob_entropy"], default="loss",
+    ap.add_argument("--path", choices=["loss", "logprob", "logprob_entropy", "sample"], default="loss",
                     help="loss: the whole hot path (default). logprob / logprob_entropy: oapl_logprob_fwd alone, "
-                         "without / with the policy-entropy output (forward scoring only)")
+                         "without / with the policy-entropy output (forward scoring only). "
+                         "sample: oapl_sample_tokens (Gumbel-max draws at the workload's token temperature)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-tokens", type=int, default=2048)
     ap.add_argument("--calibration-copy", action="store_true",
@@ -127,6 +128,8 @@ def main():
     backward = cfg.backward and args.path == "loss"
 
     def step():
+        if args.path == "sample":
+            return oapl.sample_tokens(batch.H, batch.W, cfg.token_temp, 2026, workspace=ws)
         if args.path != "loss":
             return oapl.logprob_fwd(batch.H, batch.W, batch.tokens, want_entropy=args.path == "logprob_entropy",
                                     workspace=ws)
@@ -146,7 +149,7 @@ def main():
     kt = oapl.timing_read()
     oapl.timing_enable(False)
     status = oapl.read_device_status(ws)
-    loss = float(res.loss.item()) if args.path == "loss" else float(res[0].sum().item())
+    loss = float(res.loss.item()) if args.path == "loss" else float(res[0].double().sum().item())
     if args.calibration_copy:
         x = torch.ones(1 << 28, dtype=torch.float32, device=dev)
         y = torch.empty_like(x)
@@ -187,7 +190,7 @@ def main():
 
     out = {
         "metric": "rollout tokens/s for OAPL logprob+loss fwd+bwd; % of bf16 MFMA peak" if args.path == "loss"
-        else f"rollout tokens/s for oapl_logprob_fwd ({args.path}); % of bf16 MFMA peak",
+        else f"rollout tokens/s for the forward-only entry point ({args.path}); % of bf16 MFMA peak",
         "value": tokens_per_s, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": cfg.dtype, "data": "synthetic",
@@ -195,7 +198,7 @@ def main():
                                f"T={T} packed tokens, beta={cfg.beta}, {'fwd+bwd' if backward else 'fwd only'}"},
         "algorithmic_tflops": alg_tflops, "frac_of_bf16_peak_algorithmic": alg_tflops / PEAK_BF16_TFLOPS,
         "executed_tflops": hw_tflops, "frac_of_bf16_peak_executed": hw_tflops / PEAK_BF16_TFLOPS,
-        "kernels": kernels, "roofline": roofline, "loss" if args.path == "loss" else "logprob_sum": loss,
+        "kernels": kernels, "roofline": roofline, "loss" if args.path == "loss" else "output_checksum": loss,
     }
     if not args.no_cpu_baseline and args.path == "loss":
         out["cpu_baseline"] = cpu_baseline(batch, args.cpu_sample_tokens)

@@ -112,6 +112,30 @@ int32_t oapl_logprob_fwd(const void* H, const void* W, const int32_t* tokens,
                          void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * Sampling step of Alg. 1 ("sample a batch from pi_vllm") on the same fused
+ * LM head, for harnesses that need rollouts' tokens without an inference
+ * engine: one draw per row from softmax(z_t / temperature) (the appendix's
+ * generation settings are temperature 1, top-p 1) by the Gumbel-max
+ * construction,
+ *
+ *     tokens_out[t] = argmax_v ( z_{t,v} / temperature + g_{t,v} ),   ties to the smaller v,
+ *     g_{t,v} = -ln(-ln u_{t,v}),  u = ((x >> 9) + 1/2) 2^-23,
+ *     x = word (v mod 4) of Philox-4x32-10( counter = (v / 4, t mod 2^32, t / 2^32, 0),
+ *                                           key = (seed mod 2^32, seed / 2^32) ),
+ *
+ * so a draw depends only on (seed, t, v) and can be reproduced anywhere.  The
+ * logits are never stored.
+ *   temperature > 0 and finite (else OAPL_ERR_BETA)
+ *   tokens_out [T] int32
+ *   score_out  [T] float or NULL: the winning perturbed logit
+ * Workspace: oapl_workspace_bytes(T, d, V, 0, 1, dtype, 0).
+ */
+int32_t oapl_sample_tokens(const void* H, const void* W, int64_t T, int32_t d, int32_t V,
+                           int32_t dtype, float temperature, uint64_t seed,
+                           int32_t* tokens_out, float* score_out,
+                           void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * OAPL objective and gradients on one packed batch (Sec. 3.1).
  *
  *   Delta_s = sum_{t in rollout s} (logprob[t] - logq[t])     ln pi(y|x)/pi_vllm(y|x), no length normalisation
@@ -181,9 +205,9 @@ int32_t oapl_read_device_status(const void* workspace, void* stream, int32_t* st
 
 /*
  * Measurement aid, not part of the method.  The path's time is spent in four
- * dense bf16 kernels: 0 = LM-head contraction fused with the streaming
+ * dense bf16 kernels of the loss path (and a fifth for sampling): 0 = LM-head contraction fused with the streaming
  * log-sum-exp (forward), 1 = soft-max recompute producing the logit gradient,
- * 2 = the dH contraction, 3 = the dW contraction.  After
+ * 2 = the dH contraction, 3 = the dW contraction, 4 = the sampling kernel.  After
  * oapl_timing_enable(1), every launch of these kernels is bracketed by a pair
  * of HIP events recorded on the launch stream; oapl_timing_read waits for the
  * recorded events of one kernel and returns the summed duration (milliseconds)

@@ -34,7 +34,11 @@ is computed from the same log-soft-max.  The sampling step of Alg. 1 (draw
 y_t from softmax(z_t / temperature)) is stated as a Gumbel-max draw over a
 counter-based generator (Philox-4x32-10) so that a GPU kernel can reproduce
 the same draws; it is pinned by the generator's published known-answer
-vectors and by the draw frequencies matching the soft-max.
+vectors and by the draw frequencies matching the soft-max.  The paper's
+baseline objective, GRPO with token-level importance sampling (Sec. 2), is
+stated on the same log-probs; pins: zero loss and the closed-form gradient
+coefficients when all three policies agree, flat clipped branches, and finite
+differences.
 
 Pins (tests/test_oracle_pins.py): brute-force soft-max on tiny vocabularies in
 50-digit arithmetic, W = 0 giving -ln V, shift and permutation invariances,
@@ -48,6 +52,8 @@ value the paper prints exists for this path (it prints no worked example), so
 full-size numbers are pinned by these properties only.
 """
 from __future__ import annotations
+
+import math
 
 import numpy as np
 import mpmath
@@ -326,4 +332,83 @@ def oapl_forward_backward(H, W, tokens, logq, seq_offsets, rewards, group_ids,
         dH[a:b] = dZ @ W64
         dW += dZ.T @ H64[a:b]
     res.update(coeff=c, dH=dH, dW=dW)
+    return res
+
+
+# --------------------------------------------------------------------------
+# The paper's baseline objective on the same head: GRPO with token-level
+# importance sampling (Sec. 2, the displayed GRPO equation)
+# --------------------------------------------------------------------------
+
+def grpo_advantages(rewards, group_ids, n_groups: int, adv_eps: float = 1e-6) -> np.ndarray:
+    """Normalised advantage of each rollout inside its prompt's group:
+    A_i = (r_i - mean_g r) / (std_g r + adv_eps), population standard deviation."""
+    r = _f64(rewards)
+    gid = np.asarray(group_ids).astype(np.int64)
+    if gid.size and (gid.min() < 0 or gid.max() >= n_groups):
+        raise ValueError("group id outside [0, n_groups)")
+    A = np.empty_like(r)
+    for g in range(n_groups):
+        sel = gid == g
+        if not sel.any():
+            raise ValueError(f"group {g} has no rollouts")
+        rg = r[sel]
+        mean = rg.sum() / rg.size
+        std = math.sqrt(((rg - mean) ** 2).sum() / rg.size)
+        A[sel] = (rg - mean) / (std + adv_eps)
+    return A
+
+
+def grpo_token_terms(lp, logp_old, logq, adv_t, clip_eps: float):
+    """Per token: IS_t * min(r_t A_t, clip(r_t, 1 - eps, 1 + eps) A_t) and its derivative with
+    respect to ln pi(y_t), where r_t = pi / pi_old and IS_t = pi_old / pi_vllm."""
+    r = np.exp(_f64(lp) - _f64(logp_old))
+    w_is = np.exp(_f64(logp_old) - _f64(logq))
+    unclipped = r * adv_t
+    clipped = np.clip(r, 1.0 - clip_eps, 1.0 + clip_eps) * adv_t
+    term = w_is * np.minimum(unclipped, clipped)
+    dterm = np.where(unclipped <= clipped, w_is * unclipped, 0.0)    # d(r A)/d ln pi = r A; the clipped branch is flat
+    return term, dterm
+
+
+def grpo_forward_backward(H, W, tokens, logq, logp_old, seq_offsets, rewards, group_ids, n_groups: int,
+                          clip_eps: float = 0.2, adv_eps: float = 1e-6, loss_scale: float = 1.0,
+                          backward: bool = True, slab: int = 256):
+    """loss = -loss_scale * sum_x (1/G_x) sum_{y in group x} (1/|y|) sum_t IS_t min(r_t A, clip(r_t) A)
+    (the objective of Sec. 2 is maximised, so its negative is the loss; empty rollouts contribute 0)
+    and its gradients with respect to H and W.  Returns a dict like oapl_forward_backward."""
+    H64, W64 = _f64(H), _f64(W)
+    T, d = H64.shape
+    V = W64.shape[0]
+    tokens = np.asarray(tokens).astype(np.int64)
+    off = check_offsets(seq_offsets, T)
+    gid = np.asarray(group_ids).astype(np.int64)
+    lp, lse = token_logprobs(H64, W64, tokens, slab=slab)
+    A = grpo_advantages(rewards, gid, n_groups, adv_eps)
+    G = np.bincount(gid, minlength=n_groups).astype(np.float64)
+    n_seq = off.size - 1
+    loss = 0.0
+    c = np.zeros(T, dtype=np.float64)
+    for s_ in range(n_seq):
+        a, b = int(off[s_]), int(off[s_ + 1])
+        if b == a:
+            continue
+        term, dterm = grpo_token_terms(lp[a:b], _f64(logp_old)[a:b], _f64(logq)[a:b], A[s_], clip_eps)
+        w = float(loss_scale) / (G[gid[s_]] * (b - a))
+        loss -= w * float(term.sum())
+        c[a:b] = -w * dterm
+    res = dict(logprob=lp, lse=lse, advantages=A, loss=loss, coeff=c)
+    if not backward:
+        return res
+    dH = np.empty((T, d), dtype=np.float64)
+    dW = np.zeros((V, d), dtype=np.float64)
+    for a in range(0, T, slab):
+        b = min(T, a + slab)
+        p = np.exp(H64[a:b] @ W64.T - lse[a:b, None])
+        dZ = -p
+        dZ[np.arange(b - a), tokens[a:b]] += 1.0
+        dZ *= c[a:b, None]
+        dH[a:b] = dZ @ W64
+        dW += dZ.T @ H64[a:b]
+    res.update(dH=dH, dW=dW)
     return res

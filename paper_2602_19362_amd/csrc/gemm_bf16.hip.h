@@ -28,6 +28,7 @@
 #pragma once
 
 #include "common.hip.h"
+#include "rng.hip.h"
 
 namespace oapl {
 
@@ -418,6 +419,110 @@ k_fwd_lse(const bf16_t* __restrict__ Wp, const bf16_t* __restrict__ Hp, int V, i
       }
       partials[(int64_t)split * T + n0 + n_l] = make_float2(a.x, a.y);
       if (ENT) upart[(int64_t)split * T + n0 + n_l] = ua;
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------
+// Sampling (the data-generation step of Alg. 1, as a kernel on the same fused
+// head): y_t = argmax_v (z_tv / temperature + g_tv), g a standard Gumbel variate
+// drawn from Philox-4x32-10 with key = seed and counter (v / 4, t, 0), which is a
+// draw from softmax(z_t / temperature).  Same streaming structure as the forward
+// kernel: a workgroup owns a token tile and a split of the vocabulary tiles and
+// carries per token the best (score, index) so far; the 4 consecutive vocabulary
+// rows a lane owns in each accumulator quad are exactly one Philox block.
+// Ties go to the smaller index.  Output: one (score, index) pair per token and
+// split (index bit-cast into the pair's second float).
+// ---------------------------------------------------------------------------
+template <class C>
+__global__ void __launch_bounds__(C::NT)
+k_fwd_sample(const bf16_t* __restrict__ Wp, const bf16_t* __restrict__ Hp, int V, int64_t T, int n_kt, int n_splits,
+             float inv_temperature, uint32_t seed_lo, uint32_t seed_hi, float2* __restrict__ partials) {
+  extern __shared__ __attribute__((aligned(1024))) char smem_raw[];
+  lds_char_ptr smem = (lds_char_ptr)smem_raw;
+
+  const int n_tiles = (int)((T + C::BN - 1) / C::BN);
+  const int total = n_tiles * n_splits;
+  const int L = xcd_logical_id(blockIdx.x, total);
+  if (L >= total) return;
+  const int nt = L / n_splits, split = L % n_splits;
+  const int MT = (V + C::BM - 1) / C::BM;
+  const int mt_begin = (int)((int64_t)split * MT / n_splits);
+  const int mt_end = (int)((int64_t)(split + 1) * MT / n_splits);
+  const int64_t n0 = (int64_t)nt * C::BN;
+  const int64_t strip_elems = (int64_t)n_kt * (kPackBlockBytes / 2);
+
+  Mainloop<C> ml;
+  ml.setup();
+  ml.set_b(Hp + nt * strip_elems, n_kt);
+
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int wm = wave / C::WN, wn = wave % C::WN;
+  const int h = lane >> 5;
+
+  float best[C::TN];
+  int arg[C::TN];
+#pragma unroll
+  for (int j = 0; j < C::TN; ++j) { best[j] = -__builtin_inff(); arg[j] = 0x7FFFFFFF; }
+
+  f32x16 acc[C::TM][C::TN];
+  if (mt_begin < mt_end) {
+    ml.set_a(Wp + mt_begin * strip_elems, n_kt);
+    ml.start(smem);
+  }
+  for (int mt = mt_begin; mt < mt_end; ++mt) {
+    const int m0 = mt * C::BM;
+    zero_acc<C>(acc);
+    ml.finish(smem, n_kt, acc);
+    if (mt + 1 < mt_end) {
+      ml.set_a(Wp + (mt + 1) * strip_elems, n_kt);
+      ml.start(smem);
+    }
+    const int row0 = m0 + wm * C::TM * 32 + 4 * h;
+#pragma unroll
+    for (int j = 0; j < C::TN; ++j) {
+      const int64_t t = n0 + wn * C::TN * 32 + j * 32 + (lane & 31);
+      const uint32_t t_lo = (uint32_t)t, t_hi = (uint32_t)(t >> 32);
+#pragma unroll
+      for (int i = 0; i < C::TM; ++i)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const int v0 = row0 + i * 32 + 8 * q;          // multiple of 4: one Philox block
+          uint32_t x[4];
+          philox4x32_10((uint32_t)(v0 >> 2), t_lo, t_hi, 0u, seed_lo, seed_hi, x);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const float sc = __builtin_fmaf(acc[i][j][4 * q + e], inv_temperature, gumbel_from_bits(x[e]));
+            if (v0 + e < V && sc > best[j]) { best[j] = sc; arg[j] = v0 + e; }   // indices rise: strict > keeps the smallest
+          }
+        }
+    }
+  }
+
+  // merge the two lane halves, then the WM waves stacked along the vocabulary (through LDS)
+#pragma unroll
+  for (int j = 0; j < C::TN; ++j) {
+    const float so = __shfl_xor(best[j], 32, 64);
+    const int io = __shfl_xor(arg[j], 32, 64);
+    if (better(so, io, best[j], arg[j])) { best[j] = so; arg[j] = io; }
+  }
+  typedef float f32x2 __attribute__((ext_vector_type(2)));
+  __attribute__((address_space(3))) f32x2* red = (__attribute__((address_space(3))) f32x2*)smem;
+  if (h == 0) {
+#pragma unroll
+    for (int j = 0; j < C::TN; ++j)
+      red[wm * C::BN + wn * C::TN * 32 + j * 32 + lane] = f32x2{best[j], __int_as_float(arg[j])};
+  }
+  __syncthreads();
+  for (int n_l = threadIdx.x; n_l < C::BN; n_l += C::NT) {
+    if (n0 + n_l < T) {
+      f32x2 a = red[n_l];
+#pragma unroll
+      for (int w = 1; w < C::WM; ++w) {
+        const f32x2 b = red[w * C::BN + n_l];
+        if (better(b.x, __float_as_int(b.y), a.x, __float_as_int(a.y))) a = b;
+      }
+      partials[(int64_t)split * T + n0 + n_l] = make_float2(a.x, a.y);
     }
   }
 }

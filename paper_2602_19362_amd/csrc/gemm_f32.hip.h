@@ -5,6 +5,7 @@
 #pragma once
 
 #include "common.hip.h"
+#include "rng.hip.h"
 
 namespace oapl {
 
@@ -80,6 +81,38 @@ struct EpiLseF32 {
         parts[part * T + m + i] = make_float2(ref, s);
         if (upart) upart[part * T + m + i] = u;
       }
+    }
+  }
+};
+
+// Sampling: M = tokens, N = vocabulary.  Per token row and 64-column tile the best perturbed logit
+// z / temperature + Gumbel(Philox(seed; v / 4, t)) and its vocabulary index; parts[tile][t].
+struct EpiSampleF32 {
+  float2* parts;
+  int64_t T;
+  float inv_temperature;
+  uint32_t seed_lo, seed_hi;
+  __device__ void operator()(float (&acc)[4][4], int64_t m, int64_t n, int64_t M, int64_t N) const {
+    const int64_t part = n >> 6;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int64_t t = m + i;
+      uint32_t x[4];
+      philox4x32_10((uint32_t)(n >> 2), (uint32_t)t, (uint32_t)(t >> 32), 0u, seed_lo, seed_hi, x);
+      float best = -__builtin_inff();
+      int arg = 0x7FFFFFFF;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const float sc = __builtin_fmaf(acc[i][j], inv_temperature, gumbel_from_bits(x[j]));
+        if (n + j < N && sc > best) { best = sc; arg = (int)(n + j); }
+      }
+#pragma unroll
+      for (int o = 8; o > 0; o >>= 1) {
+        const float so = __shfl_xor(best, o, 64);
+        const int io = __shfl_xor(arg, o, 64);
+        if (better(so, io, best, arg)) { best = so; arg = io; }
+      }
+      if ((threadIdx.x & 15) == 0 && t < M) parts[part * T + t] = make_float2(best, __int_as_float(arg));
     }
   }
 };

@@ -122,7 +122,7 @@ static inline unsigned grid1d(int64_t n, int per) { return (unsigned)((n + per -
 
 // Optional per-kernel timing of the four dense kernels: when switched on, every
 // launch is bracketed by a pair of events recorded on the launch stream itself.
-enum DenseKernel { kFwdLse = 0, kBwdDz = 1, kBwdDh = 2, kBwdDw = 3, kNumDense = 4 };
+enum DenseKernel { kFwdLse = 0, kBwdDz = 1, kBwdDh = 2, kBwdDw = 3, kFwdSample = 4, kNumDense = 5 };
 struct TimingState {
   std::mutex mu;
   bool on = false;
@@ -166,7 +166,7 @@ static bool prepare_kernels() {
   static bool ok = false;
   std::call_once(once, [] {
     ok = allow_big_lds(k_fwd_lse<Cfg, false>, Cfg::LDS_BYTES) && allow_big_lds(k_fwd_lse<Cfg, true>, Cfg::LDS_BYTES) &&
-         allow_big_lds(k_bwd_dz<Cfg>, Cfg::LDS_BYTES) &&
+         allow_big_lds(k_fwd_sample<Cfg>, Cfg::LDS_BYTES) && allow_big_lds(k_bwd_dz<Cfg>, Cfg::LDS_BYTES) &&
          allow_big_lds(k_bwd_dh<Cfg>, Cfg::LDS_BYTES) && allow_big_lds(k_bwd_dw<Cfg>, Cfg::LDS_BYTES);
   });
   return ok;
@@ -408,6 +408,50 @@ int32_t oapl_logprob_fwd(const void* H, const void* W, const int32_t* tokens, in
   if (int rc = check_workspace(workspace, workspace_bytes, p.total)) return rc;
   return forward_scores(p, H, W, tokens, nullptr, logprob_out, lse_out, entropy_out, (char*)workspace, false,
                         (hipStream_t)stream);
+}
+
+int32_t oapl_sample_tokens(const void* H, const void* W, int64_t T, int32_t d, int32_t V, int32_t dtype,
+                           float temperature, uint64_t seed, int32_t* tokens_out, float* score_out, void* workspace,
+                           size_t workspace_bytes, void* stream) {
+  if (dtype != OAPL_F32 && dtype != OAPL_BF16) return OAPL_ERR_DTYPE;
+  Plan p;
+  if (!make_plan(p, T, d, V, 0, 1, dtype, false)) return OAPL_ERR_SHAPE;
+  if (!W) return OAPL_ERR_NULL;
+  if (T > 0 && (!H || !tokens_out)) return OAPL_ERR_NULL;
+  if (!(temperature > 0.f) || !isfinite(temperature)) return OAPL_ERR_BETA;
+  if (int rc = check_workspace(workspace, workspace_bytes, p.total)) return rc;
+  hipStream_t st = (hipStream_t)stream;
+  char* ws = (char*)workspace;
+  k_fill_i32<<<1, 64, 0, st>>>((int*)(ws + p.off_status), kStatusWords, 0);
+  OAPL_LAUNCH_CHECK();
+  if (T == 0) return OAPL_OK;
+  float2* partials = (float2*)(ws + p.off_partials);
+  const float inv_t = 1.0f / temperature;
+  const uint32_t s_lo = (uint32_t)seed, s_hi = (uint32_t)(seed >> 32);
+  if (dtype == OAPL_BF16) {
+    if (!prepare_kernels()) return OAPL_ERR_HIP;
+    bf16_t* Wp = (bf16_t*)(ws + p.off_Wp);
+    bf16_t* Hp = (bf16_t*)(ws + p.off_Hp);
+    k_pack_rows<<<dim3(p.n_kt_d, p.n_rt_v), 256, 0, st>>>((const bf16_t*)W, V, d, d, Wp, p.n_kt_d);
+    OAPL_LAUNCH_CHECK();
+    k_pack_rows<<<dim3(p.n_kt_d, (unsigned)p.n_rt_T), 256, 0, st>>>((const bf16_t*)H, T, d, d, Hp, p.n_kt_d);
+    OAPL_LAUNCH_CHECK();
+    const int64_t total = p.n_rt_T * p.n_parts;
+    {
+      ScopedKernelTimer tm(kFwdSample, st);
+      k_fwd_sample<Cfg><<<(unsigned)round_up(total, 8), Cfg::NT, Cfg::LDS_BYTES, st>>>(
+          Wp, Hp, V, T, p.n_kt_d, p.n_parts, inv_t, s_lo, s_hi, partials);
+    }
+    OAPL_LAUNCH_CHECK();
+  } else {
+    F32Operand A{(const float*)H, d, 1}, B{(const float*)W, d, 1};
+    dim3 grid(grid1d(V, 64), grid1d(T, 64));
+    k_gemm_f32<<<grid, 256, 0, st>>>(A, B, T, (int64_t)V, (int64_t)d, EpiSampleF32{partials, T, inv_t, s_lo, s_hi});
+    OAPL_LAUNCH_CHECK();
+  }
+  k_sample_finish<<<grid1d(T, 256), 256, 0, st>>>(partials, p.n_parts, T, tokens_out, score_out);
+  OAPL_LAUNCH_CHECK();
+  return OAPL_OK;
 }
 
 int32_t oapl_loss_fwd_bwd(const void* H, const void* W, const int32_t* tokens, const float* logq,

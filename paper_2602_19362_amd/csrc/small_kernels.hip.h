@@ -5,6 +5,7 @@
 #pragma once
 
 #include "common.hip.h"
+#include "rng.hip.h"
 
 namespace oapl {
 
@@ -89,6 +90,22 @@ k_lse_finish(const float2* __restrict__ partials, int n_parts, int64_t Ttok, con
     omp_ws[t] = ok ? (float)omp : 0.f;
     inv_omp_ws[t] = ok ? (float)(1.0 / omp) : 0.f;
   }
+}
+
+// Picks, per token, the best (score, index) pair over the vocabulary splits (ties to the smaller index).
+__global__ void __launch_bounds__(256)
+k_sample_finish(const float2* __restrict__ partials, int n_parts, int64_t Ttok, int32_t* __restrict__ tokens_out,
+                float* __restrict__ score_out) {
+  const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (t >= Ttok) return;
+  float best = -__builtin_inff();
+  int arg = 0x7FFFFFFF;
+  for (int p = 0; p < n_parts; ++p) {
+    const float2 a = partials[(int64_t)p * Ttok + t];
+    if (better(a.x, __float_as_int(a.y), best, arg)) { best = a.x; arg = __float_as_int(a.y); }
+  }
+  tokens_out[t] = arg;
+  if (score_out) score_out[t] = best;
 }
 
 // out[s] = sum_{t in [off[s], off[s+1])} x[t] in double: one workgroup per

@@ -33,6 +33,9 @@ _SIGNATURES = {
     "oapl_logprob_fwd": (_c.c_int32, [_c.c_void_p, _c.c_void_p, _c.c_void_p, _c.c_int64, _c.c_int32, _c.c_int32,
                                       _c.c_int32, _c.c_void_p, _c.c_void_p, _c.c_void_p, _c.c_void_p, _c.c_size_t,
                                       _c.c_void_p]),
+    "oapl_sample_tokens": (_c.c_int32, [_c.c_void_p, _c.c_void_p, _c.c_int64, _c.c_int32, _c.c_int32, _c.c_int32,
+                                        _c.c_float, _c.c_uint64, _c.c_void_p, _c.c_void_p, _c.c_void_p, _c.c_size_t,
+                                        _c.c_void_p]),
     "oapl_loss_fwd_bwd": (_c.c_int32, [_c.c_void_p] * 7 + [_c.c_int64] + [_c.c_int32] * 5 + [_c.c_float] * 2 +
                           [_c.c_void_p] * 7 + [_c.c_size_t, _c.c_void_p]),
     "oapl_loss_fwd_bwd_two_beta": (_c.c_int32, [_c.c_void_p] * 7 + [_c.c_int64] + [_c.c_int32] * 5 + [_c.c_float] * 3 +
@@ -43,7 +46,7 @@ _SIGNATURES = {
     "oapl_timing_read": (_c.c_int32, [_c.c_int32, _c.POINTER(_c.c_double), _c.POINTER(_c.c_int64)]),
 }
 
-DENSE_KERNELS = ("k_fwd_lse", "k_bwd_dz", "k_bwd_dh", "k_bwd_dw")
+DENSE_KERNELS = ("k_fwd_lse", "k_bwd_dz", "k_bwd_dh", "k_bwd_dw", "k_fwd_sample")
 
 _lib = None
 
@@ -151,6 +154,29 @@ def logprob_fwd(H: torch.Tensor, W: torch.Tensor, tokens: torch.Tensor, *, want_
     if rc != 0:
         raise OaplError(rc, "oapl_logprob_fwd")
     return tuple(x for x in (logprob, lse, ent) if x is not None) + (ws,)
+
+
+def sample_tokens(H: torch.Tensor, W: torch.Tensor, temperature: float, seed: int, *, want_scores: bool = False,
+                  workspace: Optional[torch.Tensor] = None):
+    """oapl_sample_tokens: one Gumbel-max draw per row from softmax(H W^T / temperature)."""
+    dt = _dtype_code(H)
+    T, d = H.shape
+    V = W.shape[0]
+    if W.shape[1] != d:
+        raise ValueError("shape mismatch between H and W")
+    dev = H.device
+    nbytes = workspace_bytes(T, d, V, 0, 1, dt, False)
+    if nbytes == 0:
+        raise OaplError(2, "oapl_workspace_bytes")
+    ws = _workspace(nbytes, dev, workspace)
+    tokens = torch.empty(T, dtype=torch.int32, device=dev)
+    scores = torch.empty(T, dtype=torch.float32, device=dev) if want_scores else None
+    rc = lib().oapl_sample_tokens(_dev(H, H.dtype, "H", dev), _dev(W, H.dtype, "W", dev), T, d, V, dt,
+                                  float(temperature), int(seed) & 0xFFFFFFFFFFFFFFFF, tokens.data_ptr(),
+                                  scores.data_ptr() if want_scores else None, ws.data_ptr(), ws.numel(), _stream(dev))
+    if rc != 0:
+        raise OaplError(rc, "oapl_sample_tokens")
+    return (tokens, scores, ws) if want_scores else (tokens, ws)
 
 
 class LossResult(NamedTuple):

@@ -51,6 +51,8 @@ def test_workspace_bytes_host_logic():
     assert wb(256, 64, 0, 8, 2, 0, False) == 0
     assert wb(256, 64, 1024, 8, 0, 0, False) == 0
     assert wb(256, 64, 1024, 8, 2, 5, False) == 0
+    assert wb(256, 64, (1 << 21) + 1, 8, 2, 0, False) == 0 and wb(256, (1 << 21) + 8, 1024, 8, 2, 0, False) == 0
+    assert wb(65535 * 256 + 1, 64, 1024, 8, 2, oapl.OAPL_BF16, False) == 0
     assert wb(256, 60, 1024, 8, 2, oapl.OAPL_BF16, False) == 0     # bf16 rows must be 16-byte multiples
     assert wb(0, 64, 1024, 0, 1, oapl.OAPL_BF16, True) > 0          # an empty batch is legal
 
@@ -76,6 +78,11 @@ def test_host_side_errors_return_before_any_launch():
     assert loss(dtype=9) == 3 and loss(n_groups=0) == 2 and loss(ws_bytes=64) == 7
     assert L.oapl_loss_fwd_bwd_two_beta(one, one, one, one, one, one, one, 4, 8, 8, 2, 1, 0, 1.0, 0.0, 1.0,
                                         one, None, None, None, one, one, one, 1 << 24, None) == 6
+    # sampling: temperature must be positive and finite
+    assert L.oapl_sample_tokens(one, one, 4, 8, 8, 0, 0.0, 1, one, None, one, 1 << 20, None) == 6
+    assert L.oapl_sample_tokens(one, one, 4, 8, 8, 0, float("nan"), 1, one, None, one, 1 << 20, None) == 6
+    assert L.oapl_sample_tokens(one, one, 4, 8, 8, 0, 1.0, 1, None, None, one, 1 << 20, None) == 1
+    assert L.oapl_sample_tokens(one, one, 4, 8, 8, 3, 1.0, 1, one, None, one, 1 << 20, None) == 3
     assert L.oapl_segmented_sum_f32(None, one, 3, one, None) == 1
     assert L.oapl_segmented_sum_f32(one, one, -1, one, None) == 2
     assert L.oapl_segmented_sum_f32(None, None, 0, None, None) == 0

@@ -98,6 +98,14 @@ def test_full_size_configuration(name):
         assert np.abs(f64(ent[rt]) - ent_ref).max() <= 2e-2
         assert float(ent.min()) >= 0.0 and float(ent.max()) <= np.log(V) + 1e-4
         del lp2, ent, ws2
+        # ... and the sampling kernel at the configuration's own temperature (tokens ~ softmax(z / 0.8))
+        from tests.test_gpu_parity import _check_samples
+        tok, sc, ws3 = oapl.sample_tokens(b.H, b.W, cfg.token_temp, 2026, want_scores=True)
+        torch.cuda.synchronize()
+        assert oapl.read_device_status(ws3) == 0
+        n_diff = _check_samples(b.H, b.W, cfg.token_temp, 2026, tok, sc, rows=rows)
+        print(f"[{name}] sampled draws checked={rows.size} near-tie differences={n_diff}", flush=True)
+        del tok, sc, ws3
     vstar_ref = orc.group_value_estimate(f64(b.rewards), b.group_ids.cpu().numpy(), b.n_groups, b.beta)
     assert np.abs(f64(res.vstar) - vstar_ref).max() <= 1e-6
     if name == "r1_14b":      # forced all-fail / all-pass prompts: the estimate is the reward itself

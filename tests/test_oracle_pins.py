@@ -482,3 +482,84 @@ def test_rollouts_with_zero_residual_get_zero_gradient():
     assert np.abs(res["dH"][a:b]).max() < 1e-12
     others = np.r_[0:a, b:off[-1]]
     assert np.abs(res["dH"][others]).max() > 1e-3
+
+
+# ------------------------------------------------------------------- GRPO --
+
+def _grpo_problem(seed):
+    H, W, tok, logq, off, r, gid, P = _tiny_problem(seed, T_per=(3, 2, 4, 0, 2, 3), d=3, V=7)
+    r = np.array([1.0, 0.0, 0.0, 1.0, 1.0, 0.0])       # every group has both outcomes
+    rng = _rng(seed + 1)
+    lp, _ = orc.token_logprobs(H, W, tok)
+    logp_old = lp + rng.normal(scale=0.1, size=lp.size)
+    logq = logp_old + rng.normal(scale=0.1, size=lp.size)
+    return H, W, tok, logq, logp_old, off, r, gid, P
+
+
+def test_grpo_advantages_are_group_normalised():
+    r = np.array([1.0, 0.0, 0.0, 1.0, 1.0, 0.0, 3.0])
+    gid = np.array([0, 1, 0, 1, 0, 1, 1])
+    A = orc.grpo_advantages(r, gid, 2, adv_eps=0.0)
+    for g in (0, 1):
+        a = A[gid == g]
+        assert abs(a.mean()) < 1e-15 and abs((a ** 2).mean() - 1.0) < 1e-14      # population variance 1
+    assert A[0] == pytest.approx((1 - 2 / 3) / math.sqrt(2 / 9))
+    # all-equal rewards: zero advantage (the epsilon keeps 0 / 0 away)
+    assert orc.grpo_advantages(np.ones(4), np.zeros(4, int), 1).tolist() == [0.0] * 4
+
+
+def test_grpo_on_policy_closed_form():
+    """pi = pi_old = pi_vllm: every ratio is 1, each non-empty rollout contributes A_i / G to the
+    objective (so it is 0 when no rollout of a group is empty) and the coefficient of every token of
+    rollout i is -A_i / (G |y_i|)."""
+    H, W, tok, _, _, off, r, gid, P = _grpo_problem(90)
+    lp, _ = orc.token_logprobs(H, W, tok)
+    res = orc.grpo_forward_backward(H, W, tok, lp, lp, off, r, gid, P)
+    A = orc.grpo_advantages(r, gid, P)
+    G = np.bincount(gid, minlength=P)
+    nonempty = np.diff(off) > 0
+    assert res["loss"] == pytest.approx(-sum(A[s] / G[gid[s]] for s in range(len(r)) if nonempty[s]), rel=1e-13)
+    # without the empty rollout the normalised advantages of each group cancel
+    keep = np.nonzero(nonempty)[0]
+    off2 = np.concatenate([[0], np.cumsum(np.diff(off)[keep])])
+    res2 = orc.grpo_forward_backward(H, W, tok, lp, lp, off2, r[keep], gid[keep], P)
+    assert abs(res2["loss"]) < 1e-14
+    for s in range(len(r)):
+        a, b = off[s], off[s + 1]
+        if b > a:
+            assert np.allclose(res["coeff"][a:b], -A[s] / (G[gid[s]] * (b - a)), rtol=1e-12)
+
+
+def test_grpo_clipped_tokens_are_flat_and_unclipped_are_not():
+    adv = np.array([2.0, 2.0, -2.0, -2.0, 2.0])
+    lp_old = np.zeros(5)
+    lp = np.log(np.array([1.5, 1.1, 0.5, 0.9, 0.7]))       # ratios r_t
+    logq = np.full(5, np.log(0.5))                          # IS = pi_old / pi_vllm = 2
+    term, dterm = orc.grpo_token_terms(lp, lp_old, logq, adv, 0.2)
+    # A > 0, r > 1 + eps: clipped at 1.2 A;  A < 0, r < 1 - eps: clipped at 0.8 A;  others r A
+    assert np.allclose(term, 2 * np.array([1.2 * 2, 1.1 * 2, 0.8 * -2, 0.9 * -2, 0.7 * 2]))
+    assert np.allclose(dterm, 2 * np.array([0.0, 1.1 * 2, 0.0, 0.9 * -2, 0.7 * 2]))
+
+
+@pytest.mark.parametrize("seed", [91, 92])
+def test_grpo_gradients_match_finite_differences(seed):
+    H, W, tok, logq, logp_old, off, r, gid, P = _grpo_problem(seed)
+    res = orc.grpo_forward_backward(H, W, tok, logq, logp_old, off, r, gid, P, loss_scale=0.5)
+    lp = res["logprob"]
+    ratio = np.exp(lp - logp_old)
+    assert np.abs(ratio - 1.2).min() > 1e-3 and np.abs(ratio - 0.8).min() > 1e-3     # away from the kinks
+
+    def loss_of(Hx, Wx):
+        return orc.grpo_forward_backward(Hx, Wx, tok, logq, logp_old, off, r, gid, P, loss_scale=0.5,
+                                         backward=False)["loss"]
+    h = 1e-6
+    ref = max(np.abs(res["dH"]).max(), np.abs(res["dW"]).max())
+    for name, A in (("dH", H), ("dW", W)):
+        for idx in np.ndindex(A.shape):
+            Ap, Am = A.copy(), A.copy()
+            Ap[idx] += h
+            Am[idx] -= h
+            fd = (loss_of(Ap, W) - loss_of(Am, W)) / (2 * h) if name == "dH" else \
+                 (loss_of(H, Ap) - loss_of(H, Am)) / (2 * h)
+            assert abs(fd - res[name][idx]) < 2e-7 * ref + 1e-10, (name, idx, fd, res[name][idx])
+    assert np.abs(res["dW"].sum(axis=0)).max() < 1e-13
