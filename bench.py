@@ -56,7 +56,7 @@ def parse():
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="qwen7b", help="name in synth.CONFIGS")
-    ap.add_argument("--path", choices=["loss", "logprob", "logprob_entropy", "sample"], default="loss",
+    ap.add_argument("--path", choices=["loss", "grpo", "logprob", "logprob_entropy", "sample"], default="loss",
                     help="loss: the whole hot path (default). logprob / logprob_entropy: oapl_logprob_fwd alone, "
                          "without / with the policy-entropy output (forward scoring only). "
                          "sample: oapl_sample_tokens (Gumbel-max draws at the workload's token temperature)")
@@ -125,9 +125,17 @@ def main():
     dH = torch.empty_like(batch.H) if cfg.backward else None
     dW = torch.empty((V, d), dtype=torch.float32, device=dev) if cfg.backward else None
 
-    backward = cfg.backward and args.path == "loss"
+    backward = cfg.backward and args.path in ("loss", "grpo")
+    if args.path == "grpo":       # previous-policy log-probs: the engine's plus a small seeded lag
+        g = torch.Generator(device=dev)
+        g.manual_seed(synth.BASE_SEED + 977)
+        logp_old = (batch.logq + 0.05 * torch.randn(T, generator=g, device=dev)).contiguous()
 
     def step():
+        if args.path == "grpo":
+            return oapl.grpo_loss_fwd_bwd(batch.H, batch.W, batch.tokens, batch.logq, logp_old, batch.seq_offsets,
+                                          batch.rewards, batch.group_ids, batch.n_groups, backward=cfg.backward,
+                                          workspace=ws, dH=dH, dW=dW)
         if args.path == "sample":
             return oapl.sample_tokens(batch.H, batch.W, cfg.token_temp, 2026, workspace=ws)
         if args.path != "loss":
@@ -149,7 +157,7 @@ def main():
     kt = oapl.timing_read()
     oapl.timing_enable(False)
     status = oapl.read_device_status(ws)
-    loss = float(res.loss.item()) if args.path == "loss" else float(res[0].double().sum().item())
+    loss = float(res.loss.item()) if args.path in ("loss", "grpo") else float(res[0].double().sum().item())
     if args.calibration_copy:
         x = torch.ones(1 << 28, dtype=torch.float32, device=dev)
         y = torch.empty_like(x)
@@ -190,7 +198,7 @@ def main():
 
     out = {
         "metric": "rollout tokens/s for OAPL logprob+loss fwd+bwd; % of bf16 MFMA peak" if args.path == "loss"
-        else f"rollout tokens/s for the forward-only entry point ({args.path}); % of bf16 MFMA peak",
+        else "rollout tokens/s for the GRPO baseline loss fwd+bwd on the same head" if args.path == "grpo" else f"rollout tokens/s for the forward-only entry point ({args.path}); % of bf16 MFMA peak",
         "value": tokens_per_s, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": cfg.dtype, "data": "synthetic",
@@ -198,7 +206,7 @@ def main():
                                f"T={T} packed tokens, beta={cfg.beta}, {'fwd+bwd' if backward else 'fwd only'}"},
         "algorithmic_tflops": alg_tflops, "frac_of_bf16_peak_algorithmic": alg_tflops / PEAK_BF16_TFLOPS,
         "executed_tflops": hw_tflops, "frac_of_bf16_peak_executed": hw_tflops / PEAK_BF16_TFLOPS,
-        "kernels": kernels, "roofline": roofline, "loss" if args.path == "loss" else "output_checksum": loss,
+        "kernels": kernels, "roofline": roofline, "loss" if args.path in ("loss", "grpo") else "output_checksum": loss,
     }
     if not args.no_cpu_baseline and args.path == "loss":
         out["cpu_baseline"] = cpu_baseline(batch, args.cpu_sample_tokens)

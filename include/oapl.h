@@ -188,6 +188,35 @@ int32_t oapl_loss_fwd_bwd_two_beta(const void* H, const void* W, const int32_t* 
                                    void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * The paper's baseline on the same fused head: GRPO with token-level importance
+ * sampling (Sec. 2, the displayed GRPO objective; appendix: clip ratio 0.2,
+ * length normalisation on).  With A_s the group-normalised advantage of rollout s,
+ *
+ *   A_s     = (r_s - mean_g r) / (std_g r + adv_eps)          population std over the prompt's group
+ *   r_t     = pi(y_t) / pi_old(y_t) = exp(logprob[t] - logp_old[t])
+ *   IS_t    = pi_old(y_t) / pi_vllm(y_t) = exp(logp_old[t] - logq[t])
+ *   loss    = - loss_scale * sum_g (1/G_g) sum_{s in g} (1/|y_s|) sum_{t in s}
+ *                 IS_t min( r_t A_s, clip(r_t, 1 - clip_eps, 1 + clip_eps) A_s )
+ *
+ * (the objective is maximised in the paper; the loss is its negative; empty
+ * rollouts contribute 0), and dH, dW = d loss / dH, d loss / dW with pi_old,
+ * pi_vllm and A constants: tokens on a clipped branch get zero gradient.  The
+ * paper does not spell out the normalisation of A: population standard
+ * deviation plus adv_eps is this library's reading.
+ *   logp_old [T] float: log-probs of the tokens under the previous trainer policy
+ *   0 <= clip_eps < 1, adv_eps >= 0, all finite (else OAPL_ERR_BETA)
+ *   adv_out [n_seq] float or NULL; other arguments as for oapl_loss_fwd_bwd.
+ */
+int32_t oapl_grpo_loss_fwd_bwd(const void* H, const void* W, const int32_t* tokens,
+                               const float* logq, const float* logp_old, const int64_t* seq_offsets,
+                               const float* rewards, const int32_t* group_ids,
+                               int64_t T, int32_t d, int32_t V, int32_t n_seq, int32_t n_groups,
+                               int32_t dtype, float clip_eps, float adv_eps, float loss_scale,
+                               float* loss_out, float* logprob_out, float* adv_out,
+                               void* dH, float* dW,
+                               void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * Per-rollout sums over a packed stream (the reduction behind Delta_s in
  * Eq. 3), exposed on its own: out[s] = sum_{t in [off[s], off[s+1])} x[t],
  * accumulated in double in a fixed order (bit-reproducible).

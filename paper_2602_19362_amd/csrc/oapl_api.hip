@@ -36,7 +36,7 @@ struct Plan {
   int n_rt_v = 0, n_rt_d = 0, n_kt_d = 0, n_kt_v = 0, n_kt_g = 0, n_kt_t = 0;
   int64_t n_rt_T = 0;
   size_t off_status = 0, off_partials = 0, off_upart = 0, off_zy = 0, off_lse2 = 0, off_diff = 0, off_coef = 0, off_delta = 0,
-         off_cseq = 0, off_vstar = 0, off_omp = 0, off_inv = 0, off_Wp = 0, off_Hp = 0, off_WTp = 0, off_HTp = 0,
+         off_cseq = 0, off_vstar = 0, off_gw = 0, off_omp = 0, off_inv = 0, off_Wp = 0, off_Hp = 0, off_WTp = 0, off_HTp = 0,
          off_G = 0, off_GT = 0, total = 0;
 };
 
@@ -99,7 +99,8 @@ static bool make_plan(Plan& p, int64_t T, int d, int V, int n_seq, int n_groups,
   p.off_inv = take(Tn * 4);
   p.off_delta = take((size_t)(n_seq > 0 ? n_seq : 1) * 8);
   p.off_cseq = take((size_t)(n_seq > 0 ? n_seq : 1) * 4);
-  p.off_vstar = take((size_t)n_groups * 8);
+  p.off_vstar = take((size_t)n_groups * 16);
+  p.off_gw = take((size_t)((n_seq > 0 ? n_seq : 1) + n_groups) * 8);
   if (dtype == OAPL_BF16) {
     p.off_Wp = take((size_t)p.n_rt_v * p.n_kt_d * kPackBlockBytes);
     p.off_Hp = take((size_t)p.n_rt_T * p.n_kt_d * kPackBlockBytes);
@@ -368,6 +369,53 @@ static int loss_impl(const void* H, const void* W, const int32_t* tokens, const 
   return backward_grads(p, H, W, tokens, dH, dW, ws, st);
 }
 
+// The paper's baseline objective on the same fused head (Sec. 2): forward scores, group advantages,
+// clipped importance-weighted token terms, then the same recompute backward with other coefficients.
+static int grpo_impl(const void* H, const void* W, const int32_t* tokens, const float* logq, const float* logp_old,
+                     const int64_t* seq_offsets, const float* rewards, const int32_t* group_ids, int64_t T, int32_t d,
+                     int32_t V, int32_t n_seq, int32_t n_groups, int32_t dtype, float clip_eps, float adv_eps,
+                     float loss_scale, float* loss_out, float* logprob_out, float* adv_out, void* dH, float* dW,
+                     void* workspace, size_t workspace_bytes, void* stream) {
+  if (dtype != OAPL_F32 && dtype != OAPL_BF16) return OAPL_ERR_DTYPE;
+  const bool bwd = (dH != nullptr) || (dW != nullptr);
+  Plan p;
+  if (!make_plan(p, T, d, V, n_seq, n_groups, dtype, bwd)) return OAPL_ERR_SHAPE;
+  if (!W || !seq_offsets || !loss_out || (bwd && (!dW || (T > 0 && !dH)))) return OAPL_ERR_NULL;
+  if (T > 0 && (!H || !tokens || !logq || !logp_old)) return OAPL_ERR_NULL;
+  if (n_seq > 0 && (!rewards || !group_ids)) return OAPL_ERR_NULL;
+  if (!(clip_eps >= 0.f) || !(clip_eps < 1.f) || !(adv_eps >= 0.f) || !isfinite(adv_eps) || !isfinite(loss_scale))
+    return OAPL_ERR_BETA;
+  if (int rc = check_workspace(workspace, workspace_bytes, p.total)) return rc;
+
+  hipStream_t st = (hipStream_t)stream;
+  char* ws = (char*)workspace;
+  if (int rc = forward_scores(p, H, W, tokens, logq, logprob_out, nullptr, nullptr, ws, true, st)) return rc;
+
+  int* status = (int*)(ws + p.off_status);
+  float* adv = (float*)(ws + p.off_cseq);
+  double* gstat = (double*)(ws + p.off_vstar);          // [2 n_groups]: mean, std
+  double* wseq = (double*)(ws + p.off_gw);              // [n_seq + n_groups]
+  double* seqterm = (double*)(ws + p.off_delta);
+  float* coef = (float*)(ws + p.off_coef);
+  k_grpo_advantage<<<1, 256, 0, st>>>(rewards, group_ids, seq_offsets, n_seq, n_groups, T, (double)adv_eps,
+                                      (double)loss_scale, gstat, gstat + n_groups, adv, wseq, adv_out, status);
+  OAPL_LAUNCH_CHECK();
+  if (T > 0) {
+    k_fill_f32<<<grid1d(T, 256 * 8), 256, 0, st>>>(coef, T, 0.f);
+    OAPL_LAUNCH_CHECK();
+  }
+  if (n_seq > 0) {
+    const float* factor = (bwd && p.dtype == OAPL_BF16) ? (const float*)(ws + p.off_omp) : nullptr;
+    k_grpo_tokens<<<n_seq, 256, 0, st>>>((const double*)(ws + p.off_diff), logq, logp_old, seq_offsets, n_seq, T, adv,
+                                         wseq, (double)clip_eps, factor, coef, seqterm);
+    OAPL_LAUNCH_CHECK();
+  }
+  k_grpo_loss<<<1, 64, 0, st>>>(seqterm, n_seq, status, loss_out);
+  OAPL_LAUNCH_CHECK();
+  if (!bwd) return OAPL_OK;
+  return backward_grads(p, H, W, tokens, dH, dW, ws, st);
+}
+
 }  // namespace oapl
 
 using namespace oapl;
@@ -474,6 +522,17 @@ int32_t oapl_loss_fwd_bwd_two_beta(const void* H, const void* W, const int32_t* 
   return loss_impl(H, W, tokens, logq, seq_offsets, rewards, group_ids, T, d, V, n_seq, n_groups, dtype, beta_value,
                    beta_loss, loss_scale, loss_out, logprob_out, seq_logratio_out, vstar_out, dH, dW, workspace,
                    workspace_bytes, stream);
+}
+
+int32_t oapl_grpo_loss_fwd_bwd(const void* H, const void* W, const int32_t* tokens, const float* logq,
+                               const float* logp_old, const int64_t* seq_offsets, const float* rewards,
+                               const int32_t* group_ids, int64_t T, int32_t d, int32_t V, int32_t n_seq,
+                               int32_t n_groups, int32_t dtype, float clip_eps, float adv_eps, float loss_scale,
+                               float* loss_out, float* logprob_out, float* adv_out, void* dH, float* dW,
+                               void* workspace, size_t workspace_bytes, void* stream) {
+  return grpo_impl(H, W, tokens, logq, logp_old, seq_offsets, rewards, group_ids, T, d, V, n_seq, n_groups, dtype,
+                   clip_eps, adv_eps, loss_scale, loss_out, logprob_out, adv_out, dH, dW, workspace, workspace_bytes,
+                   stream);
 }
 
 int32_t oapl_segmented_sum_f32(const float* x, const int64_t* seq_offsets, int32_t n_seq, double* out, void* stream) {

@@ -205,6 +205,101 @@ k_group_value_loss(const double* __restrict__ Delta, const float* __restrict__ r
   }
 }
 
+// GRPO baseline (Sec. 2, the displayed GRPO objective), group step: the normalised advantage
+//   A_s = (r_s - mean_g r) / (std_g r + adv_eps)     (population standard deviation of the group)
+// and the weight w_s = scale / (G_g |y_s|) of rollout s (0 for an empty rollout).  One workgroup;
+// validates offsets and group ids like the OAPL kernel and records the status.
+__global__ void __launch_bounds__(256)
+k_grpo_advantage(const float* __restrict__ rewards, const int32_t* __restrict__ gid, const int64_t* __restrict__ off,
+                 int n_seq, int n_groups, int64_t Ttok, double adv_eps, double scale, double* __restrict__ gmean,
+                 double* __restrict__ gstd, float* __restrict__ adv, double* __restrict__ wseq,
+                 float* __restrict__ adv_out, int* __restrict__ err) {
+  __shared__ int bad;
+  const int tid = threadIdx.x;
+  if (tid == 0) bad = 0;
+  __syncthreads();
+  if (tid == 0 && (off[0] != 0 || off[n_seq] != Ttok)) atomicCAS(&bad, 0, kErrOffsets);
+  for (int s = tid; s < n_seq; s += 256) {
+    if (off[s + 1] < off[s]) atomicCAS(&bad, 0, kErrOffsets);
+    if (gid[s] < 0 || gid[s] >= n_groups) atomicCAS(&bad, 0, kErrGroup);
+  }
+  for (int g = tid; g < n_groups; g += 256) {
+    double sum = 0.0;
+    int cnt = 0;
+    for (int s = 0; s < n_seq; ++s)
+      if (gid[s] == g) { sum += (double)rewards[s]; ++cnt; }
+    if (cnt == 0) {
+      atomicCAS(&bad, 0, kErrGroup);
+      gmean[g] = __builtin_nan("");
+      gstd[g] = __builtin_nan("");
+      continue;
+    }
+    const double mean = sum / cnt;
+    double var = 0.0;
+    for (int s = 0; s < n_seq; ++s)
+      if (gid[s] == g) { const double dlt = (double)rewards[s] - mean; var += dlt * dlt; }
+    gmean[g] = mean;
+    gstd[g] = sqrt(var / cnt);
+    wseq[n_seq + g] = (double)cnt;   // group sizes live behind the per-rollout weights
+  }
+  __threadfence_block();
+  __syncthreads();
+  for (int s = tid; s < n_seq; s += 256) {
+    const int g = gid[s];
+    const bool ok = g >= 0 && g < n_groups && !bad;
+    const double a = ok ? ((double)rewards[s] - gmean[g]) / (gstd[g] + adv_eps) : __builtin_nan("");
+    const int64_t len = off[s + 1] - off[s];
+    adv[s] = (float)a;
+    if (adv_out) adv_out[s] = (float)a;
+    wseq[s] = (ok && len > 0) ? scale / (wseq[n_seq + g] * (double)len) : 0.0;
+  }
+  if (tid == 0 && bad) record_error(err, bad);
+}
+
+// GRPO, token step: one workgroup per rollout.  With r_t = pi / pi_old and IS_t = pi_old / pi_vllm,
+//   term_t = IS_t min(r_t A, clip(r_t, 1 - eps, 1 + eps) A),   d term_t / d ln pi(y_t) = IS_t r_t A if unclipped else 0,
+// it writes the loss gradient coefficient c_t = -w_s d term_t (times factor[t] if given) and the
+// rollout's loss share -w_s sum_t term_t (double, fixed order).  lp comes as diff = lp - logq in double.
+__global__ void __launch_bounds__(256)
+k_grpo_tokens(const double* __restrict__ diff, const float* __restrict__ logq, const float* __restrict__ logp_old,
+              const int64_t* __restrict__ off, int n_seq, int64_t Ttok, const float* __restrict__ adv,
+              const double* __restrict__ wseq, double clip_eps, const float* __restrict__ factor,
+              float* __restrict__ coef, double* __restrict__ seqterm) {
+  __shared__ double wsum[4];
+  const int s = blockIdx.x;
+  if (s >= n_seq) return;
+  int64_t a = off[s], b = off[s + 1];
+  a = a < 0 ? 0 : (a > Ttok ? Ttok : a);
+  b = b < a ? a : (b > Ttok ? Ttok : b);
+  const double A = (double)adv[s], w = wseq[s];
+  double acc = 0.0;
+  for (int64_t t = a + threadIdx.x; t < b; t += 256) {
+    const double q = (double)logq[t], lo = (double)logp_old[t];
+    const double lp = diff[t] + q;
+    const double r = exp(lp - lo), is = exp(lo - q);
+    const double unclipped = r * A;
+    const double rc = r < 1.0 - clip_eps ? 1.0 - clip_eps : (r > 1.0 + clip_eps ? 1.0 + clip_eps : r);
+    const double clipped = rc * A;
+    acc += is * (unclipped <= clipped ? unclipped : clipped);
+    const double g = unclipped <= clipped ? -w * is * unclipped : 0.0;
+    coef[t] = (float)(factor ? g * (double)factor[t] : g);
+  }
+  acc = wave_sum(acc);
+  if ((threadIdx.x & 63) == 0) wsum[threadIdx.x >> 6] = acc;
+  __syncthreads();
+  if (threadIdx.x == 0) seqterm[s] = -w * (((wsum[0] + wsum[1]) + wsum[2]) + wsum[3]);
+}
+
+// loss = sum_s seqterm[s] in rollout order (one thread: n_seq is small), NaN if a data error was recorded.
+__global__ void k_grpo_loss(const double* __restrict__ seqterm, int n_seq, const int* __restrict__ err,
+                            float* __restrict__ loss_out) {
+  if (threadIdx.x != 0 || blockIdx.x != 0) return;
+  double loss = 0.0;
+  for (int s = 0; s < n_seq; ++s) loss += seqterm[s];
+  if (*err == kErrOffsets || *err == kErrGroup) loss = __builtin_nan("");
+  loss_out[0] = (float)loss;
+}
+
 // coef[t] = cseq[s(t)] (times factor[t] if given): one workgroup per rollout
 // writes its token range (clamped to [0, T], so malformed offsets cannot write
 // out of bounds).

@@ -40,6 +40,8 @@ _SIGNATURES = {
                           [_c.c_void_p] * 7 + [_c.c_size_t, _c.c_void_p]),
     "oapl_loss_fwd_bwd_two_beta": (_c.c_int32, [_c.c_void_p] * 7 + [_c.c_int64] + [_c.c_int32] * 5 + [_c.c_float] * 3 +
                                    [_c.c_void_p] * 7 + [_c.c_size_t, _c.c_void_p]),
+    "oapl_grpo_loss_fwd_bwd": (_c.c_int32, [_c.c_void_p] * 8 + [_c.c_int64] + [_c.c_int32] * 5 + [_c.c_float] * 3 +
+                               [_c.c_void_p] * 6 + [_c.c_size_t, _c.c_void_p]),
     "oapl_segmented_sum_f32": (_c.c_int32, [_c.c_void_p, _c.c_void_p, _c.c_int32, _c.c_void_p, _c.c_void_p]),
     "oapl_read_device_status": (_c.c_int32, [_c.c_void_p, _c.c_void_p, _c.POINTER(_c.c_int32)]),
     "oapl_timing_enable": (_c.c_int32, [_c.c_int32]),
@@ -232,6 +234,54 @@ def loss_fwd_bwd(H, W, tokens, logq, seq_offsets, rewards, group_ids, n_groups: 
     if rc != 0:
         raise OaplError(rc, where)
     return LossResult(loss, logprob, seq_lr, vstar, dH, dW, ws)
+
+
+class GrpoResult(NamedTuple):
+    loss: torch.Tensor            # [1] float32
+    logprob: torch.Tensor         # [T] float32
+    advantages: torch.Tensor      # [N] float32
+    dH: Optional[torch.Tensor]
+    dW: Optional[torch.Tensor]
+    workspace: torch.Tensor
+
+
+def grpo_loss_fwd_bwd(H, W, tokens, logq, logp_old, seq_offsets, rewards, group_ids, n_groups: int, *,
+                      clip_eps: float = 0.2, adv_eps: float = 1e-6, loss_scale: float = 1.0, backward: bool = True,
+                      workspace: Optional[torch.Tensor] = None, dH: Optional[torch.Tensor] = None,
+                      dW: Optional[torch.Tensor] = None) -> GrpoResult:
+    """oapl_grpo_loss_fwd_bwd: the paper's GRPO + token-level importance sampling baseline."""
+    dt = _dtype_code(H)
+    T, d = H.shape
+    V = W.shape[0]
+    n_seq = rewards.shape[0]
+    if W.shape[1] != d or tokens.shape != (T,) or logq.shape != (T,) or logp_old.shape != (T,) \
+            or seq_offsets.shape != (n_seq + 1,) or group_ids.shape != (n_seq,):
+        raise ValueError("shape mismatch between the inputs")
+    dev = H.device
+    nbytes = workspace_bytes(T, d, V, n_seq, n_groups, dt, backward)
+    if nbytes == 0:
+        raise OaplError(2, "oapl_workspace_bytes")
+    ws = _workspace(nbytes, dev, workspace)
+    loss = torch.empty(1, dtype=torch.float32, device=dev)
+    logprob = torch.empty(T, dtype=torch.float32, device=dev)
+    adv = torch.empty(n_seq, dtype=torch.float32, device=dev)
+    if backward:
+        dH = torch.empty_like(H) if dH is None else dH
+        dW = torch.empty((V, d), dtype=torch.float32, device=dev) if dW is None else dW
+        if dH.shape != H.shape or dW.shape != (V, d):
+            raise ValueError("dH / dW have the wrong shape")
+    else:
+        dH = dW = None
+    rc = lib().oapl_grpo_loss_fwd_bwd(
+        _dev(H, H.dtype, "H", dev), _dev(W, H.dtype, "W", dev), _dev(tokens, torch.int32, "tokens", dev),
+        _dev(logq, torch.float32, "logq", dev), _dev(logp_old, torch.float32, "logp_old", dev),
+        _dev(seq_offsets, torch.int64, "seq_offsets", dev), _dev(rewards, torch.float32, "rewards", dev),
+        _dev(group_ids, torch.int32, "group_ids", dev), T, d, V, n_seq, n_groups, dt, float(clip_eps), float(adv_eps),
+        float(loss_scale), loss.data_ptr(), logprob.data_ptr(), adv.data_ptr(), _dev(dH, H.dtype, "dH", dev),
+        _dev(dW, torch.float32, "dW", dev), ws.data_ptr(), ws.numel(), _stream(dev))
+    if rc != 0:
+        raise OaplError(rc, "oapl_grpo_loss_fwd_bwd")
+    return GrpoResult(loss, logprob, adv, dH, dW, ws)
 
 
 def segmented_sum_f32(x: torch.Tensor, seq_offsets: torch.Tensor) -> torch.Tensor:

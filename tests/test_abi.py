@@ -78,6 +78,13 @@ def test_host_side_errors_return_before_any_launch():
     assert loss(dtype=9) == 3 and loss(n_groups=0) == 2 and loss(ws_bytes=64) == 7
     assert L.oapl_loss_fwd_bwd_two_beta(one, one, one, one, one, one, one, 4, 8, 8, 2, 1, 0, 1.0, 0.0, 1.0,
                                         one, None, None, None, one, one, one, 1 << 24, None) == 6
+    # GRPO baseline: clip in [0, 1), adv_eps >= 0, finite scale; gradients as a pair; logp_old required
+    def grpo(clip=0.2, eps=1e-6, scale=1.0, old=one, dH=one, dW=one, dtype=0):
+        return L.oapl_grpo_loss_fwd_bwd(one, one, one, one, old, one, one, one, 4, 8, 8, 2, 1, dtype, clip, eps,
+                                        scale, one, None, None, dH, dW, one, 1 << 24, None)
+    assert grpo(clip=1.0) == 6 and grpo(clip=-0.1) == 6 and grpo(clip=float("nan")) == 6
+    assert grpo(eps=-1.0) == 6 and grpo(eps=float("inf")) == 6 and grpo(scale=float("nan")) == 6
+    assert grpo(old=None) == 1 and grpo(dH=None) == 1 and grpo(dtype=5) == 3
     # sampling: temperature must be positive and finite
     assert L.oapl_sample_tokens(one, one, 4, 8, 8, 0, 0.0, 1, one, None, one, 1 << 20, None) == 6
     assert L.oapl_sample_tokens(one, one, 4, 8, 8, 0, float("nan"), 1, one, None, one, 1 << 20, None) == 6

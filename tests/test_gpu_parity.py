@@ -353,3 +353,103 @@ def test_peaked_logits_stay_finite():
     assert np.abs(lp - ref["logprob"]).max() <= 2e-2 * np.maximum(1.0, np.abs(ref["logprob"]).max() / 100)
     assert np.isfinite(f64(res.dH)).all() and np.isfinite(f64(res.dW)).all()
     assert rel(grad_norm(f64(res.dH), f64(res.dW)), grad_norm(ref["dH"], ref["dW"])) <= 5e-3
+
+
+# ---------------------------------------------------------------- GRPO baseline (Sec. 2) --
+
+def _grpo_inputs(b, seed):
+    """logp_old and logq for a batch: ratios pi/pi_old drawn from {e^-0.5, e^-0.05, e^0.05, e^0.5}, so that
+    every token sits well inside one branch of the clip (kinks at 0.8 and 1.2) and both branches occur."""
+    g = torch.Generator(device=DEV)
+    g.manual_seed(7000 + seed)
+    lp = synth.engine_logprobs(b.H, b.W, b.tokens)
+    steps = torch.tensor([-0.5, -0.05, 0.05, 0.5], device=DEV)
+    pick = torch.randint(0, 4, (b.T,), generator=g, device=DEV)
+    logp_old = (lp + steps[pick]).contiguous()
+    logq = (logp_old + 0.1 * torch.randn(b.T, generator=g, device=DEV)).contiguous()
+    return logq, logp_old
+
+
+def _grpo_check(b, logq, logp_old, res, lp_tol, rel_tol, g_rtol, g_atol_frac, **kw):
+    from oracle import oapl_oracle as orc
+    assert oapl.read_device_status(res.workspace) == 0
+    off = b.seq_offsets.cpu().numpy()
+    gid = b.group_ids.cpu().numpy()
+    ref = orc.grpo_forward_backward(f64(b.H), f64(b.W), b.tokens.cpu().numpy(), f64(logq), f64(logp_old), off,
+                                    f64(b.rewards), gid, b.n_groups, **kw)
+    assert np.abs(f64(res.logprob) - ref["logprob"]).max() <= lp_tol
+    assert np.abs(f64(res.advantages) - ref["advantages"]).max() <= 1e-6 * max(1.0, np.abs(ref["advantages"]).max())
+    # the per-rollout terms carry the advantage's sign and sum to about zero over a group: the loss is
+    # compared relative to the gross sum of the oracle's own per-token terms
+    A = ref["advantages"]
+    G = np.bincount(gid, minlength=b.n_groups)
+    gross = 0.0
+    for s in range(len(A)):
+        a, e = int(off[s]), int(off[s + 1])
+        if e > a:
+            term, _ = orc.grpo_token_terms(ref["logprob"][a:e], f64(logp_old)[a:e], f64(logq)[a:e], A[s],
+                                           kw.get("clip_eps", 0.2))
+            gross += kw.get("loss_scale", 1.0) * np.abs(term).sum() / (G[gid[s]] * (e - a))
+    assert abs(float(res.loss.item()) - ref["loss"]) <= rel_tol * gross
+    n_clipped = int((ref["coeff"] == 0).sum())
+    assert 0 < n_clipped < b.T                      # both branches exercised
+    if res.dH is not None:
+        dH, dW = f64(res.dH), f64(res.dW)
+        assert rel(grad_norm(dH, dW), grad_norm(ref["dH"], ref["dW"])) <= max(rel_tol, 1e-5)
+        for got, want in ((dH, ref["dH"]), (dW, ref["dW"])):
+            bound = g_rtol * np.abs(want) + g_atol_frac * np.abs(want).max()
+            assert np.all(np.abs(got - want) <= bound), float(np.abs(got - want).max())
+        clipped = torch.from_numpy(ref["coeff"] == 0).to(DEV)
+        assert float(res.dH[clipped].float().abs().max()) == 0.0     # clipped tokens: exactly no gradient
+    return ref
+
+
+def test_grpo_baseline_f32():
+    lens = [0, 1, 37, 64, 9, 129, 5, 64, 30]
+    b = _custom_batch("f32", d=72, V=1000, lens=lens, n_groups=3, seed=21, beta=1.0)
+    b.rewards = torch.tensor([1, 0, 0, 1, 1, 0, 1, 1, 0], dtype=torch.float32, device=DEV)
+    logq, logp_old = _grpo_inputs(b, 21)
+    res = oapl.grpo_loss_fwd_bwd(b.H, b.W, b.tokens, logq, logp_old, b.seq_offsets, b.rewards, b.group_ids, 3,
+                                 clip_eps=0.2, adv_eps=1e-6, loss_scale=0.5)
+    torch.cuda.synchronize()
+    _grpo_check(b, logq, logp_old, res, 1e-5, 1e-5, 1e-4, 3e-6, clip_eps=0.2, adv_eps=1e-6, loss_scale=0.5)
+    fwd = oapl.grpo_loss_fwd_bwd(b.H, b.W, b.tokens, logq, logp_old, b.seq_offsets, b.rewards, b.group_ids, 3,
+                                 clip_eps=0.2, adv_eps=1e-6, loss_scale=0.5, backward=False)
+    assert fwd.dH is None and torch.equal(fwd.loss, res.loss) and torch.equal(fwd.logprob, res.logprob)
+
+
+@pytest.mark.parametrize("d,V,lens,seed", [
+    (256, 1544, [100, 3, 0, 257, 64, 1, 200, 75], 22),
+    (320, 1000, [300, 17, 212, 1], 23),
+])
+def test_grpo_baseline_bf16(d, V, lens, seed):
+    b = _custom_batch("bf16", d=d, V=V, lens=lens, n_groups=2, seed=seed, beta=1.0)
+    b.rewards = torch.tensor([1.0, 0.0] * (len(lens) // 2), device=DEV)
+    b.group_ids = torch.tensor([0, 0, 1, 1] * (len(lens) // 4), dtype=torch.int32, device=DEV)
+    logq, logp_old = _grpo_inputs(b, seed)
+    res = oapl.grpo_loss_fwd_bwd(b.H, b.W, b.tokens, logq, logp_old, b.seq_offsets, b.rewards, b.group_ids, 2)
+    torch.cuda.synchronize()
+    _grpo_check(b, logq, logp_old, res, 2e-2, 1e-3, 2e-2, 6e-3)
+
+
+def test_grpo_degenerate_groups_and_errors():
+    b = _custom_batch("bf16", d=64, V=300, lens=[40, 24, 10, 6], n_groups=2, seed=24, beta=1.0)
+    b.group_ids = torch.tensor([0, 0, 1, 1], dtype=torch.int32, device=DEV)
+    logq, logp_old = _grpo_inputs(b, 24)
+    # every rollout of a prompt with the same reward: zero advantage, zero loss, zero gradient
+    same = torch.tensor([1.0, 1.0, 0.0, 0.0], device=DEV)
+    res = oapl.grpo_loss_fwd_bwd(b.H, b.W, b.tokens, logq, logp_old, b.seq_offsets, same, b.group_ids, 2)
+    assert oapl.read_device_status(res.workspace) == 0
+    assert res.loss.item() == 0.0 and float(res.advantages.abs().max()) == 0.0
+    assert float(res.dW.abs().max()) == 0.0 and float(res.dH.float().abs().max()) == 0.0
+    # bad offsets and group ids: status and NaN loss, no fault
+    off = b.seq_offsets.clone()
+    off[-1] = 79
+    res = oapl.grpo_loss_fwd_bwd(b.H, b.W, b.tokens, logq, logp_old, off, b.rewards, b.group_ids, 2)
+    assert oapl.read_device_status(res.workspace) == 4 and torch.isnan(res.loss.cpu()).all()
+    gid = torch.tensor([0, 0, 0, 5], dtype=torch.int32, device=DEV)
+    res = oapl.grpo_loss_fwd_bwd(b.H, b.W, b.tokens, logq, logp_old, b.seq_offsets, b.rewards, gid, 2)
+    assert oapl.read_device_status(res.workspace) == 5 and torch.isnan(res.loss.cpu()).all()
+    with pytest.raises(oapl.OaplError):
+        oapl.grpo_loss_fwd_bwd(b.H, b.W, b.tokens, logq, logp_old, b.seq_offsets, b.rewards, b.group_ids, 2,
+                               clip_eps=1.5)
