@@ -157,6 +157,7 @@ def main():
     kt = oapl.timing_read()
     oapl.timing_enable(False)
     status = oapl.read_device_status(ws)
+    two_pass = bool(backward and oapl.took_two_passes(ws))
     loss = float(res.loss.item()) if args.path in ("loss", "grpo") else float(res[0].double().sum().item())
     if args.calibration_copy:
         x = torch.ones(1 << 28, dtype=torch.float32, device=dev)
@@ -172,9 +173,11 @@ def main():
     ms_per_step = 1e3 * elapsed / args.steps
     tokens_per_s = T * args.steps / elapsed
     flop_unit = 2.0 * V * d                                  # one V x d contraction per token
-    n_contractions = 3 if backward else 1                    # logits, dH, dW (the recompute is not counted)
+    n_contractions = 3 if backward else 1                    # logits, dH, dW: what the method must compute
     alg_tflops = tokens_per_s * flop_unit * n_contractions / 1e12
-    hw_tflops = tokens_per_s * flop_unit * (4 if backward else 1) / 1e12
+    # executed: the single sweep visits the logits once (3 contractions); the two-pass schedule recomputes them (4)
+    n_executed = (4 if two_pass else 3) if backward else 1
+    hw_tflops = tokens_per_s * flop_unit * n_executed / 1e12
 
     # Each dense kernel executes 2*V*d flop per token it processes; over the
     # timed steps every kernel sees every token once per step.
@@ -206,6 +209,7 @@ def main():
                                f"T={T} packed tokens, beta={cfg.beta}, {'fwd+bwd' if backward else 'fwd only'}"},
         "algorithmic_tflops": alg_tflops, "frac_of_bf16_peak_algorithmic": alg_tflops / PEAK_BF16_TFLOPS,
         "executed_tflops": hw_tflops, "frac_of_bf16_peak_executed": hw_tflops / PEAK_BF16_TFLOPS,
+        "schedule": ("two_pass" if two_pass else "single_sweep") if backward else "forward_only",
         "kernels": kernels, "roofline": roofline, "loss" if args.path in ("loss", "grpo") else "output_checksum": loss,
     }
     if not args.no_cpu_baseline and args.path == "loss":

@@ -148,6 +148,18 @@ int32_t oapl_sample_tokens(const void* H, const void* W, int64_t T, int32_t d, i
  *               dH[t,:] = c_t (W[y_t,:] - sum_v p_{t,v} W[v,:])
  *               dW[v,:] = sum_t c_t (1[v = y_t] - p_{t,v}) H[t,:]
  *
+ * How the gradients are scheduled (bf16): the logits are visited ONCE.  Panels of
+ * at most 65536 token rows are swept with the soft-max written unnormalised
+ * (bf16, against a per-row reference exponent fixed before the sweep), their
+ * row sums give lse and the log-probs, and the dH / dW contractions consume a
+ * panel as soon as every rollout touching it is scored.  That needs (a) no
+ * rollout longer than one panel and (b) every row's largest logit within
+ * about 97 nats of the largest among its first 256 vocabulary entries and the
+ * sampled token.  Both are checked on the device; if either fails, the same
+ * call recomputes everything in two passes (log-sum-exp first, then soft-max
+ * recompute per panel), in stream order, with no host involvement.  The
+ * results of the two schedules agree to rounding.  fp32 always runs two passes.
+ *
  * The same beta is used in Eq. 2 and Eq. 3, as the method section writes
  * them.  loss_scale = 1 gives the paper's plain sum; it exists so a caller can
  * average over a batch.
@@ -233,10 +245,23 @@ int32_t oapl_segmented_sum_f32(const float* x, const int64_t* seq_offsets, int32
 int32_t oapl_read_device_status(const void* workspace, void* stream, int32_t* status_out);
 
 /*
- * Measurement aid, not part of the method.  The path's time is spent in four
- * dense bf16 kernels of the loss path (and a fifth for sampling): 0 = LM-head contraction fused with the streaming
- * log-sum-exp (forward), 1 = soft-max recompute producing the logit gradient,
- * 2 = the dH contraction, 3 = the dW contraction, 4 = the sampling kernel.  After
+ * Which schedule the last loss call on `workspace` ended up using: waits for
+ * `stream`, then *two_pass_out (host pointer) = 1 if the device sent the call
+ * down the two-pass path, 0 if the single sweep was valid (also 0 for calls
+ * that never try the sweep: fp32, forward-only, empty).
+ * oapl_single_sweep_enable(0) makes later loss calls of the process skip the
+ * single sweep altogether (two passes always); 1 restores the default.
+ */
+int32_t oapl_read_path_taken(const void* workspace, void* stream, int32_t* two_pass_out);
+void oapl_single_sweep_enable(int32_t on);
+
+/*
+ * Measurement aid, not part of the method.  The path's time is spent in the
+ * dense bf16 kernels: 0 = LM-head contraction fused with the streaming
+ * log-sum-exp (forward-only scoring, and pass one of the two-pass loss),
+ * 1 = soft-max recompute producing the logit gradient (pass two of the two-pass loss),
+ * 2 = the dH contraction, 3 = the dW contraction, 4 = the sampling kernel,
+ * 5 = the single sweep (contraction + unnormalised soft-max panel + row sums).  After
  * oapl_timing_enable(1), every launch of these kernels is bracketed by a pair
  * of HIP events recorded on the launch stream; oapl_timing_read waits for the
  * recorded events of one kernel and returns the summed duration (milliseconds)

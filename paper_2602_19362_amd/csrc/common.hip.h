@@ -22,6 +22,11 @@ constexpr double kLn2 = 0.6931471805599453094;
 // "minus infinity" that survives (m - m) without producing NaN.
 constexpr float kNegHuge = -3.0e38f;
 
+// Packed bf16 operand layout of the MFMA kernels: blocks of 256 rows x 64 k, 32 KiB each.
+constexpr int kPackRows = 256;                          // rows of a packed block
+constexpr int kPackK = 64;                              // k-extent of a packed block
+constexpr int kPackBlockBytes = kPackRows * kPackK * 2; // 32 KiB
+
 // Status words recorded by kernels; the values are those of oapl_status.
 constexpr int kErrOffsets = 4;
 constexpr int kErrGroup = 5;
@@ -30,6 +35,18 @@ constexpr int kErrTokenRange = 9;
 // First device-side error wins; later ones are dropped.
 __device__ __forceinline__ void record_error(int* flag, int code) {
   atomicCAS(flag, 0, code);
+}
+
+// A kernel launched with a gate runs only if the flag word's truth value equals
+// `want` (flag == nullptr: always runs).  The loss entry points use it to choose,
+// on the device and in stream order, between the single-sweep path and the
+// two-pass path without a host round trip.
+struct Gate {
+  const int* flag;
+  int want;
+};
+__device__ __forceinline__ bool gate_closed(const Gate g) {
+  return g.flag != nullptr && ((*g.flag != 0) != (g.want != 0));
 }
 
 __device__ __forceinline__ float wave_sum(float v) {

@@ -32,9 +32,6 @@
 
 namespace oapl {
 
-constexpr int kPackRows = 256;                          // rows of a packed block
-constexpr int kPackK = 64;                              // k-extent of a packed block
-constexpr int kPackBlockBytes = kPackRows * kPackK * 2; // 32 KiB
 
 template <int WM_, int WN_, int TM_, int TN_, int NS_>
 struct TileCfg {
@@ -305,9 +302,10 @@ __device__ __forceinline__ void strip_tile(int L, int MT, int NTl, int& mt, int&
 template <class C, bool ENT>
 __global__ void __launch_bounds__(C::NT)
 k_fwd_lse(const bf16_t* __restrict__ Wp, const bf16_t* __restrict__ Hp, int V, int64_t T, int n_kt,
-          int n_splits, float2* __restrict__ partials, float* __restrict__ upart) {
+          int n_splits, float2* __restrict__ partials, float* __restrict__ upart, Gate gate) {
   extern __shared__ __attribute__((aligned(1024))) char smem_raw[];
   lds_char_ptr smem = (lds_char_ptr)smem_raw;
+  if (gate_closed(gate)) return;
 
   const int n_tiles = (int)((T + C::BN - 1) / C::BN);
   const int total = n_tiles * n_splits;
@@ -546,9 +544,10 @@ template <class C>
 __global__ void __launch_bounds__(C::NT)
 k_bwd_dz(const bf16_t* __restrict__ Wp, const bf16_t* __restrict__ Hp_panel, int V, int64_t n_valid, int n_kt,
          const int32_t* __restrict__ tokens, const float* __restrict__ lse2, const float* __restrict__ inv_omp,
-         bf16_t* __restrict__ Gp, int g_n_kt, bf16_t* __restrict__ GTp, int gt_n_kt) {
+         bf16_t* __restrict__ Gp, int g_n_kt, bf16_t* __restrict__ GTp, int gt_n_kt, Gate gate) {
   extern __shared__ __attribute__((aligned(1024))) char smem_raw[];
   lds_char_ptr smem = (lds_char_ptr)smem_raw;
+  if (gate_closed(gate)) return;
 
   const int MT = (V + C::BM - 1) / C::BM;
   const int NTl = (int)((n_valid + C::BN - 1) / C::BN);
@@ -634,6 +633,112 @@ k_bwd_dz(const bf16_t* __restrict__ Wp, const bf16_t* __restrict__ Hp_panel, int
 }
 
 // ---------------------------------------------------------------------------
+// Single-sweep variant of steps a1, a2 and a8: ONE pass over the logits serves
+// both the log-sum-exp and the gradient.  The soft-max is written unnormalised
+// against a per-token reference exponent ref2[t] that is known before the pass
+// (an upper-bound-free guess: the largest of a sample of the row's logits, see
+// k_sweep_ref), in the exp2 domain:
+//     Pt[t][v] = 2^(z[t][v] * log2(e) - ref2[t])          (bf16, packed twice like G above)
+//     spart[mt][t] = sum over the vocabulary tile mt of Pt[t][v]   (fp32, from the unrounded values)
+// so that, with S_t = sum_mt spart[mt][t]:  lse_t = (ref2[t] + log2 S_t) ln 2  and
+//     dL/dz[t][v] = c_t (1[v == y_t] - Pt[t][v] / S_t) = a_t * Gt[t][v],   a_t = -c_t / S_t,
+//     Gt[t][v] = Pt[t][v]  (v != y_t),    Gt[t][y_t] = Pt[t][y_t] - S_t   (patched in by k_sweep_finish).
+// The row factor a_t only exists once S_t and the rollout's residual are known, i.e. after the
+// pass; it is applied by the same consumers as f_t above (dH epilogue, transposed H).  bf16 has
+// fp32's exponent range, so the unnormalised values are as accurate as normalised ones as long
+// as the row's largest logit stays within ~2^100 of the reference; k_sweep_finish checks that
+// and otherwise sends the whole call down the two-pass path.
+// ---------------------------------------------------------------------------
+template <class C>
+__global__ void __launch_bounds__(C::NT)
+k_sweep(const bf16_t* __restrict__ Wp, const bf16_t* __restrict__ Hp_panel, int V, int64_t n_valid, int n_kt,
+        const float* __restrict__ ref2 /* panel-local */, bf16_t* __restrict__ Gp, int g_n_kt,
+        bf16_t* __restrict__ GTp, int gt_n_kt, float* __restrict__ spart /* [MT][ld_s], panel-local */,
+        int64_t ld_s, Gate gate) {
+  extern __shared__ __attribute__((aligned(1024))) char smem_raw[];
+  lds_char_ptr smem = (lds_char_ptr)smem_raw;
+  if (gate_closed(gate)) return;
+
+  const int MT = (V + C::BM - 1) / C::BM;
+  const int NTl = (int)((n_valid + C::BN - 1) / C::BN);
+  const int total = MT * NTl;
+  const int L = xcd_logical_id(blockIdx.x, total);
+  if (L >= total) return;
+  int mt, nt;
+  strip_tile<8>(L, MT, NTl, mt, nt);
+  const int m0 = mt * C::BM;
+  const int64_t n0 = (int64_t)nt * C::BN;
+  const int64_t strip_elems = (int64_t)n_kt * (kPackBlockBytes / 2);
+
+  Mainloop<C> ml;
+  ml.setup();
+  ml.set_a(Wp + mt * strip_elems, n_kt);
+  ml.set_b(Hp_panel + nt * strip_elems, n_kt);
+
+  f32x16 acc[C::TM][C::TN];
+  zero_acc<C>(acc);
+  ml.start(smem);
+  ml.finish(smem, n_kt, acc);
+
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int wm = wave / C::WN, wn = wave % C::WN;
+  const int h = lane >> 5;
+  const int row0 = m0 + wm * C::TM * 32 + 4 * h;   // first vocabulary row of this lane
+
+  if (m0 + C::BM > V) {  // ragged last vocabulary tile: rows >= V do not exist (2^(-inf) = 0 below)
+#pragma unroll
+    for (int i = 0; i < C::TM; ++i)
+#pragma unroll
+      for (int r = 0; r < 16; ++r)
+        if (row0 + acc_row(i, r) >= V) {
+#pragma unroll
+          for (int j = 0; j < C::TN; ++j) acc[i][j][r] = -__builtin_inff();
+        }
+  }
+  float csum[C::TN];
+#pragma unroll
+  for (int j = 0; j < C::TN; ++j) {
+    const int64_t n = n0 + wn * C::TN * 32 + j * 32 + (lane & 31);
+    // token columns past the panel: reference +inf, every entry 2^(-inf) = 0
+    const float r2 = n < n_valid ? ref2[n] : __builtin_inff();
+    float sum = 0.f;
+#pragma unroll
+    for (int i = 0; i < C::TM; ++i)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const float e = __builtin_amdgcn_exp2f(__builtin_fmaf(acc[i][j][r], kLog2e, -r2));
+        acc[i][j][r] = e;
+        sum += e;
+      }
+    csum[j] = sum + __shfl_xor(sum, 32, 64);     // the two lane halves hold the same token
+  }
+  // the WM waves stacked along the vocabulary, through LDS, in a fixed order
+  __attribute__((address_space(3))) float* red = (__attribute__((address_space(3))) float*)smem;
+  if (h == 0) {
+#pragma unroll
+    for (int j = 0; j < C::TN; ++j) red[wm * C::BN + wn * C::TN * 32 + j * 32 + lane] = csum[j];
+  }
+  __syncthreads();
+  for (int n_l = threadIdx.x; n_l < C::BN; n_l += C::NT) {
+    if (n0 + n_l < n_valid) {
+      float a = red[n_l];
+#pragma unroll
+      for (int w = 1; w < C::WM; ++w) a += red[w * C::BN + n_l];
+      spart[(int64_t)mt * ld_s + n0 + n_l] = a;
+    }
+  }
+  __syncthreads();
+
+  stage_nm<C>(smem, acc);
+  __syncthreads();
+  store_nm_packed<C>(smem, Gp + (int64_t)nt * g_n_kt * (kPackBlockBytes / 2), m0 / kPackK);
+  __syncthreads();
+  stage_mn<C>(smem, acc);
+  __syncthreads();
+  store_mn_packed<C>(smem, GTp + (int64_t)mt * gt_n_kt * (kPackBlockBytes / 2), (int)(n0 / kPackK));
+}
+
+// ---------------------------------------------------------------------------
 // Backward, step 2: dH[t][j] = f_t * sum_v G[t][v] * W[v][j]
 //   A = packed W^T (rows = hidden index j, k = vocabulary), B = Gp (rows = tokens), K = V.
 // ---------------------------------------------------------------------------
@@ -641,9 +746,11 @@ template <class C>
 __global__ void __launch_bounds__(C::NT)
 k_bwd_dh(const bf16_t* __restrict__ WTp, int wt_n_kt, const bf16_t* __restrict__ Gp, int g_n_kt, int d,
          int64_t n_valid, int nk /* k-blocks to contract: ceil(V / 64) */,
-         const float* __restrict__ row_factor /* f_t, panel-local */, bf16_t* __restrict__ dH /* panel's first row */) {
+         const float* __restrict__ row_factor /* f_t, panel-local */, bf16_t* __restrict__ dH /* panel's first row */,
+         Gate gate) {
   extern __shared__ __attribute__((aligned(1024))) char smem_raw[];
   lds_char_ptr smem = (lds_char_ptr)smem_raw;
+  if (gate_closed(gate)) return;
 
   const int MT = (d + C::BM - 1) / C::BM;
   const int NTl = (int)((n_valid + C::BN - 1) / C::BN);
@@ -689,9 +796,10 @@ template <class C>
 __global__ void __launch_bounds__(C::NT)
 k_bwd_dw(const bf16_t* __restrict__ HTp, const bf16_t* __restrict__ GTp, int t_n_kt /* strip pitch of both */, int d,
          int V, int nk /* k-blocks to contract: panel tokens / 64, rounded up to the tile */,
-         float* __restrict__ dW, int accumulate) {
+         float* __restrict__ dW, int accumulate, Gate gate) {
   extern __shared__ __attribute__((aligned(1024))) char smem_raw[];
   lds_char_ptr smem = (lds_char_ptr)smem_raw;
+  if (gate_closed(gate)) return;
 
   const int MT = (d + C::BM - 1) / C::BM;
   const int NTl = (V + C::BN - 1) / C::BN;
@@ -770,8 +878,9 @@ k_pack_rows(const bf16_t* __restrict__ src, int64_t R, int K, int64_t ld, bf16_t
 // through LDS.  Blocks in [0, n_jt) x [0, n_kt); zero outside [0, Ccols) x [0, R).
 __global__ void __launch_bounds__(256)
 k_pack_transposed(const bf16_t* __restrict__ src, int64_t R, int Ccols, int64_t ld, const float* __restrict__ scale,
-                  bf16_t* __restrict__ dst, int n_kt) {
+                  bf16_t* __restrict__ dst, int n_kt, Gate gate) {
   __shared__ bf16_t tile[64][kPackRows + 2];
+  if (gate_closed(gate)) return;
   const int kt = blockIdx.x, jt = blockIdx.y;
   const int64_t r0 = (int64_t)kt * kPackK;
   const int j0 = jt * kPackRows;

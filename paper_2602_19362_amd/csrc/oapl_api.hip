@@ -37,8 +37,14 @@ struct Plan {
   int64_t n_rt_T = 0;
   size_t off_status = 0, off_partials = 0, off_upart = 0, off_zy = 0, off_lse2 = 0, off_diff = 0, off_coef = 0, off_delta = 0,
          off_cseq = 0, off_vstar = 0, off_gw = 0, off_omp = 0, off_inv = 0, off_Wp = 0, off_Hp = 0, off_WTp = 0, off_HTp = 0,
-         off_G = 0, off_GT = 0, total = 0;
+         off_G = 0, off_GT = 0, off_ref2 = 0, off_spart = 0, off_G2 = 0, off_GT2 = 0, total = 0;
+  bool sweep = false;  // single-sweep loss path available (bf16 with backward)
 };
+
+constexpr int kFlagWord = 8;   // status word that selects the two-pass path on the device
+
+// Process-wide switch for the single-sweep loss path (on by default).
+static bool g_single_sweep = true;
 
 static bool make_plan(Plan& p, int64_t T, int d, int V, int n_seq, int n_groups, int dtype, bool bwd) {
   if (T < 0 || d < 1 || V < 1 || n_seq < 0 || n_groups < 1) return false;
@@ -111,6 +117,15 @@ static bool make_plan(Plan& p, int64_t T, int d, int V, int n_seq, int n_groups,
       p.off_HTp = take((size_t)p.n_rt_d * p.n_kt_t * kPackBlockBytes);
       p.off_G = take((size_t)(p.Tp / kPackRows) * p.n_kt_g * kPackBlockBytes);
       p.off_GT = take((size_t)p.n_rt_v * p.n_kt_t * kPackBlockBytes);
+      // single-sweep path: reference exponents, per-vocabulary-tile row sums of one panel, and a
+      // second panel buffer pair (a panel's gradient contractions run after the next panel's sweep)
+      p.sweep = true;
+      p.off_ref2 = take(Tn * 4);
+      p.off_spart = take((size_t)p.n_rt_v * (size_t)p.Tp * 4);
+      if (T > p.Tp) {
+        p.off_G2 = take((size_t)(p.Tp / kPackRows) * p.n_kt_g * kPackBlockBytes);
+        p.off_GT2 = take((size_t)p.n_rt_v * p.n_kt_t * kPackBlockBytes);
+      }
     } else {
       p.off_G = take((size_t)p.Tp * V * 4);
     }
@@ -123,7 +138,7 @@ static inline unsigned grid1d(int64_t n, int per) { return (unsigned)((n + per -
 
 // Optional per-kernel timing of the four dense kernels: when switched on, every
 // launch is bracketed by a pair of events recorded on the launch stream itself.
-enum DenseKernel { kFwdLse = 0, kBwdDz = 1, kBwdDh = 2, kBwdDw = 3, kFwdSample = 4, kNumDense = 5 };
+enum DenseKernel { kFwdLse = 0, kBwdDz = 1, kBwdDh = 2, kBwdDw = 3, kFwdSample = 4, kSweep = 5, kNumDense = 6 };
 struct TimingState {
   std::mutex mu;
   bool on = false;
@@ -136,7 +151,8 @@ static TimingState& timing() {
 struct ScopedKernelTimer {
   hipStream_t st;
   hipEvent_t stop = nullptr;
-  ScopedKernelTimer(int which, hipStream_t s) : st(s) {
+  ScopedKernelTimer(int which, hipStream_t s, bool enabled = true) : st(s) {
+    if (!enabled) return;
     TimingState& t = timing();
     std::lock_guard<std::mutex> g(t.mu);
     if (!t.on) return;
@@ -168,7 +184,8 @@ static bool prepare_kernels() {
   std::call_once(once, [] {
     ok = allow_big_lds(k_fwd_lse<Cfg, false>, Cfg::LDS_BYTES) && allow_big_lds(k_fwd_lse<Cfg, true>, Cfg::LDS_BYTES) &&
          allow_big_lds(k_fwd_sample<Cfg>, Cfg::LDS_BYTES) && allow_big_lds(k_bwd_dz<Cfg>, Cfg::LDS_BYTES) &&
-         allow_big_lds(k_bwd_dh<Cfg>, Cfg::LDS_BYTES) && allow_big_lds(k_bwd_dw<Cfg>, Cfg::LDS_BYTES);
+         allow_big_lds(k_bwd_dh<Cfg>, Cfg::LDS_BYTES) && allow_big_lds(k_bwd_dw<Cfg>, Cfg::LDS_BYTES) &&
+         allow_big_lds(k_sweep<Cfg>, Cfg::LDS_BYTES);
   });
   return ok;
 }
@@ -176,23 +193,17 @@ static bool prepare_kernels() {
 // Steps a1-a3 of the path: partial soft-max statistics, sampled-token logit,
 // finish.  Writes logprob / lse if wanted, and (for the loss) lse in the
 // kernels' exponent domain plus logprob - logq in double.
-static int forward_scores(const Plan& p, const void* H, const void* W, const int32_t* tokens, const float* logq,
-                          float* logprob_out, float* lse_out, float* entropy_out, char* ws, bool keep_for_loss,
-                          hipStream_t st) {
-  int* status = (int*)(ws + p.off_status);
-  float2* partials = (float2*)(ws + p.off_partials);
-  float* upart = entropy_out ? (float*)(ws + p.off_upart) : nullptr;
-  float* zy = (float*)(ws + p.off_zy);
-  float* lse2 = keep_for_loss ? (float*)(ws + p.off_lse2) : nullptr;
-  double* diff = keep_for_loss ? (double*)(ws + p.off_diff) : nullptr;
-  float* omp = keep_for_loss ? (float*)(ws + p.off_omp) : nullptr;
-  float* inv = keep_for_loss ? (float*)(ws + p.off_inv) : nullptr;
-  const int64_t T = p.T;
+constexpr Gate kNoGate{nullptr, 0};
 
+// Clears the status header, gathers the sampled tokens' logits and (bf16) packs W and H.
+static int prepare_operands(const Plan& p, const void* H, const void* W, const int32_t* tokens, char* ws,
+                            hipStream_t st) {
+  int* status = (int*)(ws + p.off_status);
+  float* zy = (float*)(ws + p.off_zy);
+  const int64_t T = p.T;
   k_fill_i32<<<1, 64, 0, st>>>(status, kStatusWords, 0);
   OAPL_LAUNCH_CHECK();
   if (T == 0) return OAPL_OK;
-
   if (p.dtype == OAPL_BF16) {
     if (!prepare_kernels()) return OAPL_ERR_HIP;
     k_gather_logit<bf16_t, float><<<grid1d(T, 4), 256, 0, st>>>((const bf16_t*)H, (const bf16_t*)W, tokens, T, p.d,
@@ -204,59 +215,86 @@ static int forward_scores(const Plan& p, const void* H, const void* W, const int
     OAPL_LAUNCH_CHECK();
     k_pack_rows<<<dim3(p.n_kt_d, (unsigned)p.n_rt_T), 256, 0, st>>>((const bf16_t*)H, T, p.d, p.d, Hp, p.n_kt_d);
     OAPL_LAUNCH_CHECK();
-    const int64_t n_tiles = (T + Cfg::BN - 1) / Cfg::BN;
-    const int64_t total = n_tiles * p.n_parts;
-    {
-      ScopedKernelTimer tm(kFwdLse, st);
-      if (entropy_out)
-        k_fwd_lse<Cfg, true><<<(unsigned)round_up(total, 8), Cfg::NT, Cfg::LDS_BYTES, st>>>(Wp, Hp, p.V, T, p.n_kt_d,
-                                                                                            p.n_parts, partials, upart);
-      else
-        k_fwd_lse<Cfg, false><<<(unsigned)round_up(total, 8), Cfg::NT, Cfg::LDS_BYTES, st>>>(
-            Wp, Hp, p.V, T, p.n_kt_d, p.n_parts, partials, nullptr);
-    }
-    OAPL_LAUNCH_CHECK();
-    k_lse_finish<true><<<grid1d(T, 256), 256, 0, st>>>(partials, p.n_parts, T, zy, logq, logprob_out, lse_out, lse2,
-                                                       diff, omp, inv, upart, entropy_out);
-    OAPL_LAUNCH_CHECK();
   } else {
     k_gather_logit<float, double><<<grid1d(T, 4), 256, 0, st>>>((const float*)H, (const float*)W, tokens, T, p.d, p.V,
                                                                 zy, status);
-    OAPL_LAUNCH_CHECK();
-    F32Operand A{(const float*)H, p.d, 1}, B{(const float*)W, p.d, 1};
-    dim3 grid(grid1d(p.V, 64), grid1d(T, 64));
-    k_gemm_f32<<<grid, 256, 0, st>>>(A, B, T, (int64_t)p.V, (int64_t)p.d, EpiLseF32{partials, T, upart});
-    OAPL_LAUNCH_CHECK();
-    k_lse_finish<false><<<grid1d(T, 256), 256, 0, st>>>(partials, p.n_parts, T, zy, logq, logprob_out, lse_out, lse2,
-                                                        diff, omp, inv, upart, entropy_out);
     OAPL_LAUNCH_CHECK();
   }
   return OAPL_OK;
 }
 
-// Steps a8-a10: panel by panel, recompute the soft-max tiles into dZ and run
-// the two gradient contractions.
+// (after prepare_operands)
+static int forward_scores(const Plan& p, const void* H, const void* W, const int32_t* tokens, const float* logq,
+                          float* logprob_out, float* lse_out, float* entropy_out, char* ws, bool keep_for_loss,
+                          hipStream_t st, Gate gate = kNoGate) {
+  float2* partials = (float2*)(ws + p.off_partials);
+  float* upart = entropy_out ? (float*)(ws + p.off_upart) : nullptr;
+  float* zy = (float*)(ws + p.off_zy);
+  float* lse2 = keep_for_loss ? (float*)(ws + p.off_lse2) : nullptr;
+  double* diff = keep_for_loss ? (double*)(ws + p.off_diff) : nullptr;
+  float* omp = keep_for_loss ? (float*)(ws + p.off_omp) : nullptr;
+  float* inv = keep_for_loss ? (float*)(ws + p.off_inv) : nullptr;
+  const int64_t T = p.T;
+  if (T == 0) return OAPL_OK;
+  const bool timed = gate.flag == nullptr;
+
+  if (p.dtype == OAPL_BF16) {
+    const bf16_t* Wp = (const bf16_t*)(ws + p.off_Wp);
+    const bf16_t* Hp = (const bf16_t*)(ws + p.off_Hp);
+    const int64_t n_tiles = (T + Cfg::BN - 1) / Cfg::BN;
+    const int64_t total = n_tiles * p.n_parts;
+    {
+      ScopedKernelTimer tm(kFwdLse, st, timed);
+      if (entropy_out)
+        k_fwd_lse<Cfg, true><<<(unsigned)round_up(total, 8), Cfg::NT, Cfg::LDS_BYTES, st>>>(
+            Wp, Hp, p.V, T, p.n_kt_d, p.n_parts, partials, upart, gate);
+      else
+        k_fwd_lse<Cfg, false><<<(unsigned)round_up(total, 8), Cfg::NT, Cfg::LDS_BYTES, st>>>(
+            Wp, Hp, p.V, T, p.n_kt_d, p.n_parts, partials, nullptr, gate);
+    }
+    OAPL_LAUNCH_CHECK();
+    k_lse_finish<true><<<grid1d(T, 256), 256, 0, st>>>(partials, p.n_parts, T, zy, logq, logprob_out, lse_out, lse2,
+                                                       diff, omp, inv, upart, entropy_out, gate);
+    OAPL_LAUNCH_CHECK();
+  } else {
+    F32Operand A{(const float*)H, p.d, 1}, B{(const float*)W, p.d, 1};
+    dim3 grid(grid1d(p.V, 64), grid1d(T, 64));
+    k_gemm_f32<<<grid, 256, 0, st>>>(A, B, T, (int64_t)p.V, (int64_t)p.d, EpiLseF32{partials, T, upart});
+    OAPL_LAUNCH_CHECK();
+    k_lse_finish<false><<<grid1d(T, 256), 256, 0, st>>>(partials, p.n_parts, T, zy, logq, logprob_out, lse_out, lse2,
+                                                        diff, omp, inv, upart, entropy_out, kNoGate);
+    OAPL_LAUNCH_CHECK();
+  }
+  return OAPL_OK;
+}
+
+// Steps a8-a10, two-pass form: panel by panel, recompute the soft-max tiles into dZ and run
+// the two gradient contractions.  `wt_packed`: W^T has been packed already by this call.
 static int backward_grads(const Plan& p, const void* H, const void* W, const int32_t* tokens, void* dH, float* dW,
-                          char* ws, hipStream_t st) {
+                          char* ws, hipStream_t st, Gate gate = kNoGate, bool wt_packed = false) {
   const int64_t T = p.T;
   const int d = p.d, V = p.V;
   const float* lse2 = (const float*)(ws + p.off_lse2);
   const float* coef = (const float*)(ws + p.off_coef);  // bf16: f_t = c_t (1 - p_y); fp32: c_t
   const float* inv = (const float*)(ws + p.off_inv);
+  const bool timed = gate.flag == nullptr;
   if (T == 0) {
-    k_fill_f32<<<1024, 256, 0, st>>>(dW, (int64_t)V * d, 0.f);
+    k_fill_f32<<<1024, 256, 0, st>>>(dW, (int64_t)V * d, 0.f, gate);
     OAPL_LAUNCH_CHECK();
     return OAPL_OK;
   }
   if (p.dtype == OAPL_BF16) {
-    const bf16_t* Wp = (const bf16_t*)(ws + p.off_Wp);   // packed by the forward pass of this call
+    const bf16_t* Wp = (const bf16_t*)(ws + p.off_Wp);   // packed by prepare_operands
     const bf16_t* Hp = (const bf16_t*)(ws + p.off_Hp);
     bf16_t* WTp = (bf16_t*)(ws + p.off_WTp);
     bf16_t* HTp = (bf16_t*)(ws + p.off_HTp);
     bf16_t* G = (bf16_t*)(ws + p.off_G);
     bf16_t* GT = (bf16_t*)(ws + p.off_GT);
-    k_pack_transposed<<<dim3(p.n_kt_v, p.n_rt_d), 256, 0, st>>>((const bf16_t*)W, V, d, d, nullptr, WTp, p.n_kt_v);
-    OAPL_LAUNCH_CHECK();
+    if (!wt_packed) {
+      k_pack_transposed<<<dim3(p.n_kt_v, p.n_rt_d), 256, 0, st>>>((const bf16_t*)W, V, d, d, nullptr, WTp, p.n_kt_v,
+                                                                  gate);
+      OAPL_LAUNCH_CHECK();
+    }
     const int MTv = p.n_rt_v, MTd = p.n_rt_d;
     const int64_t strip_d = (int64_t)p.n_kt_d * (kPackBlockBytes / 2);
     for (int64_t t0 = 0; t0 < T; t0 += p.Tp) {
@@ -265,25 +303,25 @@ static int backward_grads(const Plan& p, const void* H, const void* W, const int
       const int64_t NTl = Kt / Cfg::BN;
       // (diag(f) H)^T of this panel, packed; token columns in [nv, Kt) come out as zeros
       k_pack_transposed<<<dim3((unsigned)(Kt / kPackK), p.n_rt_d), 256, 0, st>>>(
-          (const bf16_t*)H + t0 * d, nv, d, d, coef + t0, HTp, p.n_kt_t);
+          (const bf16_t*)H + t0 * d, nv, d, d, coef + t0, HTp, p.n_kt_t, gate);
       OAPL_LAUNCH_CHECK();
       {
-        ScopedKernelTimer tm(kBwdDz, st);
+        ScopedKernelTimer tm(kBwdDz, st, timed);
         k_bwd_dz<Cfg><<<(unsigned)round_up(MTv * NTl, 8), Cfg::NT, Cfg::LDS_BYTES, st>>>(
             Wp, Hp + (t0 / kPackRows) * strip_d, V, nv, p.n_kt_d, tokens + t0, lse2 + t0, inv + t0, G, p.n_kt_g, GT,
-            p.n_kt_t);
+            p.n_kt_t, gate);
       }
       OAPL_LAUNCH_CHECK();
       {
-        ScopedKernelTimer tm(kBwdDh, st);
+        ScopedKernelTimer tm(kBwdDh, st, timed);
         k_bwd_dh<Cfg><<<(unsigned)round_up(MTd * NTl, 8), Cfg::NT, Cfg::LDS_BYTES, st>>>(
-            WTp, p.n_kt_v, G, p.n_kt_g, d, nv, p.n_kt_v, coef + t0, (bf16_t*)dH + t0 * d);
+            WTp, p.n_kt_v, G, p.n_kt_g, d, nv, p.n_kt_v, coef + t0, (bf16_t*)dH + t0 * d, gate);
       }
       OAPL_LAUNCH_CHECK();
       {
-        ScopedKernelTimer tm(kBwdDw, st);
+        ScopedKernelTimer tm(kBwdDw, st, timed);
         k_bwd_dw<Cfg><<<(unsigned)round_up((int64_t)MTd * MTv, 8), Cfg::NT, Cfg::LDS_BYTES, st>>>(
-            HTp, GT, p.n_kt_t, d, V, (int)(Kt / kPackK), dW, t0 > 0 ? 1 : 0);
+            HTp, GT, p.n_kt_t, d, V, (int)(Kt / kPackK), dW, t0 > 0 ? 1 : 0, gate);
       }
       OAPL_LAUNCH_CHECK();
     }
@@ -316,6 +354,101 @@ static int backward_grads(const Plan& p, const void* H, const void* W, const int
   return OAPL_OK;
 }
 
+// Steps a1-a3 and a8-a10 in ONE pass over the logits (bf16, T > 0).  Per panel of token rows:
+// k_sweep writes the unnormalised soft-max panel and its row sums, k_sweep_finish turns the sums
+// into log-probs; the objective's O(T) kernels (`objective`, which must fill coef[t] = c_t * nis[t]
+// for every token whose rollout is complete and may run any number of times) then give the row
+// factors, and the two gradient contractions consume the panel.  A rollout may straddle a panel
+// boundary, so a panel's contractions run after the NEXT panel's sweep (two panel buffers); by
+// then every rollout that touches it is complete, because no rollout is longer than a panel
+// (k_sweep_plan raises the fallback flag otherwise).  All kernels here run only while the flag is 0.
+template <class Objective>
+static int sweep_path(const Plan& p, const void* H, const void* W, const int32_t* tokens, const float* logq,
+                      const int64_t* seq_offsets, float* logprob_out, void* dH, float* dW, char* ws, hipStream_t st,
+                      Objective&& objective) {
+  const int64_t T = p.T;
+  const int d = p.d, V = p.V;
+  int* flag = (int*)(ws + p.off_status) + kFlagWord;
+  const Gate fast{flag, 0};
+  const bf16_t* Wp = (const bf16_t*)(ws + p.off_Wp);
+  const bf16_t* Hp = (const bf16_t*)(ws + p.off_Hp);
+  bf16_t* WTp = (bf16_t*)(ws + p.off_WTp);
+  bf16_t* HTp = (bf16_t*)(ws + p.off_HTp);
+  bf16_t* Gbuf[2] = {(bf16_t*)(ws + p.off_G), (bf16_t*)(ws + (T > p.Tp ? p.off_G2 : p.off_G))};
+  bf16_t* GTbuf[2] = {(bf16_t*)(ws + p.off_GT), (bf16_t*)(ws + (T > p.Tp ? p.off_GT2 : p.off_GT))};
+  float2* sample = (float2*)(ws + p.off_partials);
+  const float* zy = (const float*)(ws + p.off_zy);
+  float* ref2 = (float*)(ws + p.off_ref2);
+  float* spart = (float*)(ws + p.off_spart);
+  double* diff = (double*)(ws + p.off_diff);
+  float* nis = (float*)(ws + p.off_inv);
+  const float* coef = (const float*)(ws + p.off_coef);
+  const int MTv = p.n_rt_v, MTd = p.n_rt_d;
+  const int64_t strip_d = (int64_t)p.n_kt_d * (kPackBlockBytes / 2);
+  const int64_t n_tiles = (T + Cfg::BN - 1) / Cfg::BN;
+
+  k_sweep_plan<<<grid1d(p.n_seq > 0 ? p.n_seq : 1, 256), 256, 0, st>>>(seq_offsets, p.n_seq, T, p.Tp, flag);
+  OAPL_LAUNCH_CHECK();
+  k_pack_transposed<<<dim3(p.n_kt_v, p.n_rt_d), 256, 0, st>>>((const bf16_t*)W, V, d, d, nullptr, WTp, p.n_kt_v,
+                                                              kNoGate);
+  OAPL_LAUNCH_CHECK();
+  // reference exponents: running maximum over the first vocabulary tile, one workgroup per token tile
+  k_fwd_lse<Cfg, false><<<(unsigned)round_up(n_tiles, 8), Cfg::NT, Cfg::LDS_BYTES, st>>>(
+      Wp, Hp, V < Cfg::BM ? V : Cfg::BM, T, p.n_kt_d, 1, sample, nullptr, fast);
+  OAPL_LAUNCH_CHECK();
+  k_sweep_ref<<<grid1d(T, 256), 256, 0, st>>>(sample, zy, T, ref2);
+  OAPL_LAUNCH_CHECK();
+  // rows not swept yet must read as "no contribution" in the objective's kernels
+  k_fill_f64<<<grid1d(T, 256 * 8), 256, 0, st>>>(diff, T, 0.0);
+  OAPL_LAUNCH_CHECK();
+  k_fill_f32<<<grid1d(T, 256 * 8), 256, 0, st>>>(nis, T, 0.f);
+  OAPL_LAUNCH_CHECK();
+
+  const int64_t n_panels = (T + p.Tp - 1) / p.Tp;
+  auto gradients = [&](int64_t k) -> int {
+    const int64_t t0 = k * p.Tp;
+    const int64_t nv = (T - t0) < p.Tp ? (T - t0) : p.Tp;
+    const int64_t Kt = round_up(nv, Cfg::BN);
+    const int64_t NTl = Kt / Cfg::BN;
+    if (int rc = objective(fast, nis)) return rc;
+    k_pack_transposed<<<dim3((unsigned)(Kt / kPackK), p.n_rt_d), 256, 0, st>>>(
+        (const bf16_t*)H + t0 * d, nv, d, d, coef + t0, HTp, p.n_kt_t, fast);
+    OAPL_LAUNCH_CHECK();
+    {
+      ScopedKernelTimer tm(kBwdDh, st);
+      k_bwd_dh<Cfg><<<(unsigned)round_up(MTd * NTl, 8), Cfg::NT, Cfg::LDS_BYTES, st>>>(
+          WTp, p.n_kt_v, Gbuf[k & 1], p.n_kt_g, d, nv, p.n_kt_v, coef + t0, (bf16_t*)dH + t0 * d, fast);
+    }
+    OAPL_LAUNCH_CHECK();
+    {
+      ScopedKernelTimer tm(kBwdDw, st);
+      k_bwd_dw<Cfg><<<(unsigned)round_up((int64_t)MTd * MTv, 8), Cfg::NT, Cfg::LDS_BYTES, st>>>(
+          HTp, GTbuf[k & 1], p.n_kt_t, d, V, (int)(Kt / kPackK), dW, k > 0 ? 1 : 0, fast);
+    }
+    OAPL_LAUNCH_CHECK();
+    return OAPL_OK;
+  };
+  for (int64_t k = 0; k < n_panels; ++k) {
+    const int64_t t0 = k * p.Tp;
+    const int64_t nv = (T - t0) < p.Tp ? (T - t0) : p.Tp;
+    const int64_t NTl = round_up(nv, Cfg::BN) / Cfg::BN;
+    {
+      ScopedKernelTimer tm(kSweep, st);
+      k_sweep<Cfg><<<(unsigned)round_up(MTv * NTl, 8), Cfg::NT, Cfg::LDS_BYTES, st>>>(
+          Wp, Hp + (t0 / kPackRows) * strip_d, V, nv, p.n_kt_d, ref2 + t0, Gbuf[k & 1], p.n_kt_g, GTbuf[k & 1],
+          p.n_kt_t, spart, p.Tp, fast);
+    }
+    OAPL_LAUNCH_CHECK();
+    k_sweep_finish<<<grid1d(nv, 256), 256, 0, st>>>(spart, MTv, p.Tp, nv, ref2 + t0, zy + t0, logq + t0, tokens + t0,
+                                                    V, logprob_out ? logprob_out + t0 : nullptr, diff + t0, nis + t0,
+                                                    Gbuf[k & 1], p.n_kt_g, GTbuf[k & 1], p.n_kt_t, flag, fast);
+    OAPL_LAUNCH_CHECK();
+    if (k >= 1)
+      if (int rc = gradients(k - 1)) return rc;
+  }
+  return gradients(n_panels - 1);
+}
+
 static int check_workspace(const void* ws, size_t have, size_t need) {
   if (ws == nullptr || ((uintptr_t)ws & 255) != 0 || have < need) return OAPL_ERR_WORKSPACE;
   return OAPL_OK;
@@ -341,36 +474,53 @@ static int loss_impl(const void* H, const void* W, const int32_t* tokens, const 
 
   hipStream_t st = (hipStream_t)stream;
   char* ws = (char*)workspace;
-  if (int rc = forward_scores(p, H, W, tokens, logq, logprob_out, nullptr, nullptr, ws, true, st)) return rc;
-
+  int* status = (int*)(ws + p.off_status);
   double* Delta = (double*)(ws + p.off_delta);
   float* cseq = (float*)(ws + p.off_cseq);
-  if (n_seq > 0) {
-    k_segmented_sum<double><<<n_seq, 256, 0, st>>>((const double*)(ws + p.off_diff), seq_offsets, n_seq, T, Delta);
-    OAPL_LAUNCH_CHECK();
-  }
-  k_group_value_loss<<<1, 256, 0, st>>>(Delta, rewards, group_ids, seq_offsets, n_seq, n_groups, T,
-                                        (double)beta_value, (double)beta_loss, (double)loss_scale,
-                                        (double*)(ws + p.off_vstar), cseq, loss_out, seq_logratio_out, vstar_out,
-                                        (int*)(ws + p.off_status));
-  OAPL_LAUNCH_CHECK();
-  if (!bwd) return OAPL_OK;
+  float* coef = (float*)(ws + p.off_coef);
 
-  if (T > 0) {
-    float* coef = (float*)(ws + p.off_coef);
-    k_fill_f32<<<grid1d(T, 256 * 8), 256, 0, st>>>(coef, T, 0.f);
-    OAPL_LAUNCH_CHECK();
+  // Steps a4-a7 from logprob - logq [T]: per-rollout sums, Eq. 2, Eq. 3, token coefficients
+  // coef[t] = c_t * factor[t] (factor = NULL: c_t itself).
+  auto objective = [&](Gate gate, const float* factor) -> int {
     if (n_seq > 0) {
-      const float* factor = p.dtype == OAPL_BF16 ? (const float*)(ws + p.off_omp) : nullptr;
-      k_token_coefficients<<<n_seq, 256, 0, st>>>(cseq, seq_offsets, n_seq, T, factor, coef);
+      k_segmented_sum<double><<<n_seq, 256, 0, st>>>((const double*)(ws + p.off_diff), seq_offsets, n_seq, T, Delta,
+                                                     gate);
       OAPL_LAUNCH_CHECK();
     }
+    k_group_value_loss<<<1, 256, 0, st>>>(Delta, rewards, group_ids, seq_offsets, n_seq, n_groups, T,
+                                          (double)beta_value, (double)beta_loss, (double)loss_scale,
+                                          (double*)(ws + p.off_vstar), cseq, loss_out, seq_logratio_out, vstar_out,
+                                          status, gate);
+    OAPL_LAUNCH_CHECK();
+    if (bwd && T > 0) {
+      k_fill_f32<<<grid1d(T, 256 * 8), 256, 0, st>>>(coef, T, 0.f, gate);
+      OAPL_LAUNCH_CHECK();
+      if (n_seq > 0) {
+        k_token_coefficients<<<n_seq, 256, 0, st>>>(cseq, seq_offsets, n_seq, T, factor, coef, gate);
+        OAPL_LAUNCH_CHECK();
+      }
+    }
+    return OAPL_OK;
+  };
+
+  if (int rc = prepare_operands(p, H, W, tokens, ws, st)) return rc;
+  // bf16 with gradients: one sweep over the logits; the two-pass path behind it runs only if the
+  // sweep's preconditions fail on this call's data (decided on the device, in stream order)
+  const bool sweep = bwd && T > 0 && p.sweep && g_single_sweep;
+  Gate slow = kNoGate;
+  if (sweep) {
+    if (int rc = sweep_path(p, H, W, tokens, logq, seq_offsets, logprob_out, dH, dW, ws, st, objective)) return rc;
+    slow = Gate{status + kFlagWord, 1};
   }
-  return backward_grads(p, H, W, tokens, dH, dW, ws, st);
+  if (int rc = forward_scores(p, H, W, tokens, logq, logprob_out, nullptr, nullptr, ws, true, st, slow)) return rc;
+  const float* factor = (bwd && p.dtype == OAPL_BF16) ? (const float*)(ws + p.off_omp) : nullptr;
+  if (int rc = objective(slow, factor)) return rc;
+  if (!bwd) return OAPL_OK;
+  return backward_grads(p, H, W, tokens, dH, dW, ws, st, slow, sweep);
 }
 
-// The paper's baseline objective on the same fused head (Sec. 2): forward scores, group advantages,
-// clipped importance-weighted token terms, then the same recompute backward with other coefficients.
+// The paper's baseline objective on the same fused head (Sec. 2): scores, group advantages,
+// clipped importance-weighted token terms, then the same backward with other coefficients.
 static int grpo_impl(const void* H, const void* W, const int32_t* tokens, const float* logq, const float* logp_old,
                      const int64_t* seq_offsets, const float* rewards, const int32_t* group_ids, int64_t T, int32_t d,
                      int32_t V, int32_t n_seq, int32_t n_groups, int32_t dtype, float clip_eps, float adv_eps,
@@ -389,31 +539,44 @@ static int grpo_impl(const void* H, const void* W, const int32_t* tokens, const 
 
   hipStream_t st = (hipStream_t)stream;
   char* ws = (char*)workspace;
-  if (int rc = forward_scores(p, H, W, tokens, logq, logprob_out, nullptr, nullptr, ws, true, st)) return rc;
-
   int* status = (int*)(ws + p.off_status);
   float* adv = (float*)(ws + p.off_cseq);
   double* gstat = (double*)(ws + p.off_vstar);          // [2 n_groups]: mean, std
   double* wseq = (double*)(ws + p.off_gw);              // [n_seq + n_groups]
   double* seqterm = (double*)(ws + p.off_delta);
   float* coef = (float*)(ws + p.off_coef);
+
+  auto objective = [&](Gate gate, const float* factor) -> int {
+    if (T > 0) {
+      k_fill_f32<<<grid1d(T, 256 * 8), 256, 0, st>>>(coef, T, 0.f, gate);
+      OAPL_LAUNCH_CHECK();
+    }
+    if (n_seq > 0) {
+      k_grpo_tokens<<<n_seq, 256, 0, st>>>((const double*)(ws + p.off_diff), logq, logp_old, seq_offsets, n_seq, T,
+                                           adv, wseq, (double)clip_eps, factor, coef, seqterm, gate);
+      OAPL_LAUNCH_CHECK();
+    }
+    k_grpo_loss<<<1, 64, 0, st>>>(seqterm, n_seq, status, loss_out, gate);
+    OAPL_LAUNCH_CHECK();
+    return OAPL_OK;
+  };
+
+  if (int rc = prepare_operands(p, H, W, tokens, ws, st)) return rc;
   k_grpo_advantage<<<1, 256, 0, st>>>(rewards, group_ids, seq_offsets, n_seq, n_groups, T, (double)adv_eps,
-                                      (double)loss_scale, gstat, gstat + n_groups, adv, wseq, adv_out, status);
+                                      (double)loss_scale, gstat, gstat + n_groups, adv, wseq, adv_out, status,
+                                      kNoGate);
   OAPL_LAUNCH_CHECK();
-  if (T > 0) {
-    k_fill_f32<<<grid1d(T, 256 * 8), 256, 0, st>>>(coef, T, 0.f);
-    OAPL_LAUNCH_CHECK();
+  const bool sweep = bwd && T > 0 && p.sweep && g_single_sweep;
+  Gate slow = kNoGate;
+  if (sweep) {
+    if (int rc = sweep_path(p, H, W, tokens, logq, seq_offsets, logprob_out, dH, dW, ws, st, objective)) return rc;
+    slow = Gate{status + kFlagWord, 1};
   }
-  if (n_seq > 0) {
-    const float* factor = (bwd && p.dtype == OAPL_BF16) ? (const float*)(ws + p.off_omp) : nullptr;
-    k_grpo_tokens<<<n_seq, 256, 0, st>>>((const double*)(ws + p.off_diff), logq, logp_old, seq_offsets, n_seq, T, adv,
-                                         wseq, (double)clip_eps, factor, coef, seqterm);
-    OAPL_LAUNCH_CHECK();
-  }
-  k_grpo_loss<<<1, 64, 0, st>>>(seqterm, n_seq, status, loss_out);
-  OAPL_LAUNCH_CHECK();
+  if (int rc = forward_scores(p, H, W, tokens, logq, logprob_out, nullptr, nullptr, ws, true, st, slow)) return rc;
+  const float* factor = (bwd && p.dtype == OAPL_BF16) ? (const float*)(ws + p.off_omp) : nullptr;
+  if (int rc = objective(slow, factor)) return rc;
   if (!bwd) return OAPL_OK;
-  return backward_grads(p, H, W, tokens, dH, dW, ws, st);
+  return backward_grads(p, H, W, tokens, dH, dW, ws, st, slow, sweep);
 }
 
 }  // namespace oapl
@@ -454,6 +617,7 @@ int32_t oapl_logprob_fwd(const void* H, const void* W, const int32_t* tokens, in
   if (!W) return OAPL_ERR_NULL;
   if (T > 0 && (!H || !tokens || !logprob_out)) return OAPL_ERR_NULL;
   if (int rc = check_workspace(workspace, workspace_bytes, p.total)) return rc;
+  if (int rc = prepare_operands(p, H, W, tokens, (char*)workspace, (hipStream_t)stream)) return rc;
   return forward_scores(p, H, W, tokens, nullptr, logprob_out, lse_out, entropy_out, (char*)workspace, false,
                         (hipStream_t)stream);
 }
@@ -572,6 +736,18 @@ int32_t oapl_timing_read(int32_t kernel, double* total_ms, int64_t* launches) {
   }
   *total_ms = sum;
   *launches = (int64_t)t.ev[kernel].size();
+  return OAPL_OK;
+}
+
+void oapl_single_sweep_enable(int32_t on) { g_single_sweep = on != 0; }
+
+int32_t oapl_read_path_taken(const void* workspace, void* stream, int32_t* two_pass_out) {
+  if (!workspace || !two_pass_out) return OAPL_ERR_NULL;
+  if (hipStreamSynchronize((hipStream_t)stream) != hipSuccess) return OAPL_ERR_HIP;
+  int32_t v = 0;
+  if (hipMemcpy(&v, (const int32_t*)workspace + kFlagWord, sizeof(v), hipMemcpyDeviceToHost) != hipSuccess)
+    return OAPL_ERR_HIP;
+  *two_pass_out = v != 0;
   return OAPL_OK;
 }
 

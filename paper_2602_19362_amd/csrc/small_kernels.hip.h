@@ -15,7 +15,11 @@ __device__ __forceinline__ float to_f32(bf16_t x) { return (float)x; }
 __global__ void k_fill_i32(int32_t* p, int64_t n, int32_t v) {
   for (int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) p[i] = v;
 }
-__global__ void k_fill_f32(float* p, int64_t n, float v) {
+__global__ void k_fill_f32(float* p, int64_t n, float v, Gate gate = Gate{nullptr, 0}) {
+  if (gate_closed(gate)) return;
+  for (int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) p[i] = v;
+}
+__global__ void k_fill_f64(double* p, int64_t n, double v) {
   for (int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) p[i] = v;
 }
 
@@ -58,7 +62,9 @@ __global__ void __launch_bounds__(256)
 k_lse_finish(const float2* __restrict__ partials, int n_parts, int64_t Ttok, const float* __restrict__ zy,
              const float* __restrict__ logq, float* __restrict__ logprob_out, float* __restrict__ lse_out,
              float* __restrict__ lse2_ws, double* __restrict__ diff_ws, float* __restrict__ omp_ws,
-             float* __restrict__ inv_omp_ws, const float* __restrict__ upart, float* __restrict__ entropy_out) {
+             float* __restrict__ inv_omp_ws, const float* __restrict__ upart, float* __restrict__ entropy_out,
+             Gate gate) {
+  if (gate_closed(gate)) return;
   const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (t >= Ttok) return;
   float M = kNegHuge;
@@ -116,8 +122,9 @@ k_sample_finish(const float2* __restrict__ partials, int n_parts, int64_t Ttok, 
 template <class T>
 __global__ void __launch_bounds__(256)
 k_segmented_sum(const T* __restrict__ x, const int64_t* __restrict__ off, int n_seq, int64_t limit,
-                double* __restrict__ out) {
+                double* __restrict__ out, Gate gate = Gate{nullptr, 0}) {
   __shared__ double wsum[4];
+  if (gate_closed(gate)) return;
   const int s = blockIdx.x;
   if (s >= n_seq) return;
   int64_t a = off[s], b = off[s + 1];
@@ -150,9 +157,10 @@ k_group_value_loss(const double* __restrict__ Delta, const float* __restrict__ r
                    const int32_t* __restrict__ gid, const int64_t* __restrict__ off, int n_seq, int n_groups,
                    int64_t Ttok, double beta_v, double beta_l, double scale, double* __restrict__ vstar_ws,
                    float* __restrict__ cseq, float* __restrict__ loss_out, float* __restrict__ seq_logratio_out,
-                   float* __restrict__ vstar_out, int* __restrict__ err) {
+                   float* __restrict__ vstar_out, int* __restrict__ err, Gate gate) {
   __shared__ double wsum[4];
   __shared__ int bad;
+  if (gate_closed(gate)) return;
   const int tid = threadIdx.x;
   if (tid == 0) bad = 0;
   __syncthreads();
@@ -213,8 +221,9 @@ __global__ void __launch_bounds__(256)
 k_grpo_advantage(const float* __restrict__ rewards, const int32_t* __restrict__ gid, const int64_t* __restrict__ off,
                  int n_seq, int n_groups, int64_t Ttok, double adv_eps, double scale, double* __restrict__ gmean,
                  double* __restrict__ gstd, float* __restrict__ adv, double* __restrict__ wseq,
-                 float* __restrict__ adv_out, int* __restrict__ err) {
+                 float* __restrict__ adv_out, int* __restrict__ err, Gate gate) {
   __shared__ int bad;
+  if (gate_closed(gate)) return;
   const int tid = threadIdx.x;
   if (tid == 0) bad = 0;
   __syncthreads();
@@ -264,8 +273,9 @@ __global__ void __launch_bounds__(256)
 k_grpo_tokens(const double* __restrict__ diff, const float* __restrict__ logq, const float* __restrict__ logp_old,
               const int64_t* __restrict__ off, int n_seq, int64_t Ttok, const float* __restrict__ adv,
               const double* __restrict__ wseq, double clip_eps, const float* __restrict__ factor,
-              float* __restrict__ coef, double* __restrict__ seqterm) {
+              float* __restrict__ coef, double* __restrict__ seqterm, Gate gate) {
   __shared__ double wsum[4];
+  if (gate_closed(gate)) return;
   const int s = blockIdx.x;
   if (s >= n_seq) return;
   int64_t a = off[s], b = off[s + 1];
@@ -292,7 +302,8 @@ k_grpo_tokens(const double* __restrict__ diff, const float* __restrict__ logq, c
 
 // loss = sum_s seqterm[s] in rollout order (one thread: n_seq is small), NaN if a data error was recorded.
 __global__ void k_grpo_loss(const double* __restrict__ seqterm, int n_seq, const int* __restrict__ err,
-                            float* __restrict__ loss_out) {
+                            float* __restrict__ loss_out, Gate gate) {
+  if (gate_closed(gate)) return;
   if (threadIdx.x != 0 || blockIdx.x != 0) return;
   double loss = 0.0;
   for (int s = 0; s < n_seq; ++s) loss += seqterm[s];
@@ -305,7 +316,8 @@ __global__ void k_grpo_loss(const double* __restrict__ seqterm, int n_seq, const
 // out of bounds).
 __global__ void __launch_bounds__(256)
 k_token_coefficients(const float* __restrict__ cseq, const int64_t* __restrict__ off, int n_seq, int64_t Ttok,
-                     const float* __restrict__ factor, float* __restrict__ coef) {
+                     const float* __restrict__ factor, float* __restrict__ coef, Gate gate) {
+  if (gate_closed(gate)) return;
   const int s = blockIdx.x;
   if (s >= n_seq) return;
   int64_t a = off[s], b = off[s + 1];
@@ -313,6 +325,70 @@ k_token_coefficients(const float* __restrict__ cseq, const int64_t* __restrict__
   b = b < a ? a : (b > Ttok ? Ttok : b);
   const float c = cseq[s];
   for (int64_t t = a + threadIdx.x; t < b; t += 256) coef[t] = factor ? c * factor[t] : c;
+}
+
+// ---------------------------------------------------------------------------
+// Helpers of the single-sweep loss path (see k_sweep).
+// ---------------------------------------------------------------------------
+
+// The single-sweep path finishes a panel of token rows before it knows the later panels, so a
+// rollout must end at most one panel after it starts: any rollout longer than `panel_rows`
+// (or malformed offsets) raises the flag that sends the call down the two-pass path instead.
+__global__ void __launch_bounds__(256)
+k_sweep_plan(const int64_t* __restrict__ off, int n_seq, int64_t Ttok, int64_t panel_rows, int* __restrict__ flag) {
+  bool bad = threadIdx.x == 0 && blockIdx.x == 0 && (off[0] != 0 || off[n_seq] != Ttok);
+  for (int s = blockIdx.x * 256 + threadIdx.x; s < n_seq; s += gridDim.x * 256) {
+    const int64_t len = off[s + 1] - off[s];
+    bad |= len < 0 || len > panel_rows;
+  }
+  if (bad) atomicCAS(flag, 0, 1);
+}
+
+// Reference exponent of a token row for k_sweep: the largest logit among a sample of the row
+// (the first vocabulary tile, whose running maximum `sample` carries in .x, and the sampled
+// token's own logit) plus a margin, in the exp2 domain.  Some entry of the row then equals
+// 2^-margin, so S_t >= 2^-margin, and entries down to 2^-(126 - margin) of the row's largest
+// stay normal bf16 numbers.
+constexpr float kSweepMargin = 40.f;
+constexpr float kSweepLimit = 1.2676506e30f;   // 2^100: largest S_t the single sweep accepts
+__global__ void __launch_bounds__(256)
+k_sweep_ref(const float2* __restrict__ sample, const float* __restrict__ zy, int64_t Ttok, float* __restrict__ ref2) {
+  const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (t >= Ttok) return;
+  ref2[t] = fmaxf(sample[t].x, zy[t] * kLog2e) + kSweepMargin;    // fmaxf drops a NaN zy (token out of range)
+}
+
+// Finishes one panel of the single sweep.  Per token row (panel-local index n, global t0 + n):
+//   S = sum of the vocabulary-tile partial sums (double, tile order),  lse = (ref2 + log2 S) ln 2,
+//   logprob = min(z_y - lse, 0),  diff = logprob - logq,  nis = -1 / S  (row factor of the gradient),
+// and patches the sampled token's entry of the unnormalised soft-max panel, in both packed
+// copies, to  Pt[y] - S = -S (1 - p_y)  (computed from expm1 so it is accurate when p_y -> 1).
+// Rows whose sum left the accepted range raise the fallback flag.
+__global__ void __launch_bounds__(256)
+k_sweep_finish(const float* __restrict__ spart, int n_vt, int64_t ld_s, int64_t n_valid,
+               const float* __restrict__ ref2, const float* __restrict__ zy, const float* __restrict__ logq,
+               const int32_t* __restrict__ tokens, int V, float* __restrict__ logprob_out,
+               double* __restrict__ diff, float* __restrict__ nis, bf16_t* __restrict__ Gp, int g_n_kt,
+               bf16_t* __restrict__ GTp, int gt_n_kt, int* __restrict__ flag, Gate gate) {
+  if (gate_closed(gate)) return;
+  const int64_t n = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (n >= n_valid) return;
+  double S = 0.0;
+  for (int mt = 0; mt < n_vt; ++mt) S += (double)spart[(int64_t)mt * ld_s + n];
+  if (!(S <= (double)kSweepLimit)) atomicCAS(flag, 0, 1);     // also catches inf and NaN
+  const double lse = ((double)ref2[n] + log2(S)) * kLn2;
+  double lp = (double)zy[n] - lse;     // NaN if the token was out of range
+  if (lp > 0.0) lp = 0.0;
+  if (logprob_out) logprob_out[n] = (float)lp;
+  diff[n] = lp - (double)logq[n];
+  nis[n] = (float)(-1.0 / S);
+  const int y = tokens[n];
+  if (y >= 0 && y < V) {
+    const bf16_t patch = (bf16_t)(float)(S * expm1(lp));       // -S (1 - p_y)
+    const int64_t blk = kPackRows * kPackK;                    // elements of a packed block
+    Gp[((n >> 8) * g_n_kt + (y >> 6)) * blk + (n & 255) * kPackK + (y & 63)] = patch;
+    GTp[(((int64_t)(y >> 8)) * gt_n_kt + (n >> 6)) * blk + (y & 255) * kPackK + (n & 63)] = patch;
+  }
 }
 
 }  // namespace oapl

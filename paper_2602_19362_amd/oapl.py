@@ -44,11 +44,13 @@ _SIGNATURES = {
                                [_c.c_void_p] * 6 + [_c.c_size_t, _c.c_void_p]),
     "oapl_segmented_sum_f32": (_c.c_int32, [_c.c_void_p, _c.c_void_p, _c.c_int32, _c.c_void_p, _c.c_void_p]),
     "oapl_read_device_status": (_c.c_int32, [_c.c_void_p, _c.c_void_p, _c.POINTER(_c.c_int32)]),
+    "oapl_read_path_taken": (_c.c_int32, [_c.c_void_p, _c.c_void_p, _c.POINTER(_c.c_int32)]),
+    "oapl_single_sweep_enable": (None, [_c.c_int32]),
     "oapl_timing_enable": (_c.c_int32, [_c.c_int32]),
     "oapl_timing_read": (_c.c_int32, [_c.c_int32, _c.POINTER(_c.c_double), _c.POINTER(_c.c_int64)]),
 }
 
-DENSE_KERNELS = ("k_fwd_lse", "k_bwd_dz", "k_bwd_dh", "k_bwd_dw", "k_fwd_sample")
+DENSE_KERNELS = ("k_fwd_lse", "k_bwd_dz", "k_bwd_dh", "k_bwd_dw", "k_fwd_sample", "k_sweep")
 
 _lib = None
 
@@ -127,6 +129,20 @@ def read_device_status(workspace: torch.Tensor) -> int:
     if rc != 0:
         raise OaplError(rc, "oapl_read_device_status")
     return int(out.value)
+
+
+def took_two_passes(workspace: torch.Tensor) -> bool:
+    """oapl_read_path_taken: True if the last loss call on this workspace fell back to the two-pass schedule."""
+    out = ctypes.c_int32(0)
+    rc = lib().oapl_read_path_taken(workspace.data_ptr(), _stream(workspace.device), ctypes.byref(out))
+    if rc != 0:
+        raise OaplError(rc, "oapl_read_path_taken")
+    return bool(out.value)
+
+
+def single_sweep_enable(on: bool) -> None:
+    """oapl_single_sweep_enable: process-wide switch of the single-sweep loss schedule (default on)."""
+    lib().oapl_single_sweep_enable(1 if on else 0)
 
 
 def logprob_fwd(H: torch.Tensor, W: torch.Tensor, tokens: torch.Tensor, *, want_lse: bool = False,

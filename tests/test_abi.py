@@ -38,13 +38,15 @@ def test_workspace_bytes_host_logic():
     small = wb(256, 64, 1024, 8, 2, oapl.OAPL_F32, False)
     assert small > 0 and small % 256 == 0
     assert wb(256, 64, 1024, 8, 2, oapl.OAPL_F32, True) > small
-    # the bf16 backward workspace holds two logit-gradient panels, which stop growing at the panel
-    # size; beyond that only the per-token buffers and the packed copy of H grow with T
+    # the bf16 backward workspace holds one pair of soft-max panels (tokens x V and V x tokens) when
+    # T fits one panel and two pairs beyond that; they stop growing at the panel size, after which
+    # only the per-token buffers and the packed copy of H grow with T
+    panel = 65536 * 151936 * 2
     a = wb(65536, 4096, 151936, 64, 8, oapl.OAPL_BF16, True)
     b = wb(1 << 20, 4096, 151936, 64, 8, oapl.OAPL_BF16, True)
-    assert a > 2 * 65536 * 151936 * 2
-    grow = (1 << 20) - 65536
-    assert b - a < grow * (2 * 4096 + 64)
+    c = wb(1 << 21, 4096, 151936, 64, 8, oapl.OAPL_BF16, True)
+    assert 2 * panel < a < 3 * panel and 4 * panel < b < 5 * panel
+    assert c - b < (1 << 20) * (2 * 4096 + 64)
     # invalid sizes
     assert wb(-1, 64, 1024, 8, 2, 0, False) == 0
     assert wb(256, 0, 1024, 8, 2, 0, False) == 0

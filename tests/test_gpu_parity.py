@@ -21,6 +21,25 @@ pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
 
 
+_MODE = ["single_sweep"]
+
+
+@pytest.fixture(autouse=True, params=["single_sweep", "two_pass"])
+def schedule(request):
+    """Every test of this file runs under both schedules of the bf16 loss entry points: the single
+    sweep over the logits (default) and the two-pass schedule it falls back to."""
+    _MODE[0] = request.param
+    oapl.single_sweep_enable(request.param == "single_sweep")
+    yield request.param
+    oapl.single_sweep_enable(True)
+    _MODE[0] = "single_sweep"
+
+
+def _sweep_tried(b, res):
+    """True if the call tries the single sweep first (switched on, bf16, with gradients, not empty)."""
+    return _MODE[0] == "single_sweep" and b.H.dtype == torch.bfloat16 and res.dH is not None and b.T > 0
+
+
 def _run(b, **kw):
     res = oapl.loss_fwd_bwd(b.H, b.W, b.tokens, b.logq, b.seq_offsets, b.rewards, b.group_ids, b.n_groups,
                             kw.pop("beta", b.beta), **kw)
@@ -28,8 +47,10 @@ def _run(b, **kw):
     return res
 
 
-def _check(b, res, ref, lp_tol, rel_tol, g_rtol, g_atol_frac):
+def _check(b, res, ref, lp_tol, rel_tol, g_rtol, g_atol_frac, fallback=False):
     assert oapl.read_device_status(res.workspace) == 0
+    # the schedule that served the call is the one the test means to exercise
+    assert oapl.took_two_passes(res.workspace) == (fallback and _sweep_tried(b, res))
     lp = f64(res.logprob)
     assert np.abs(lp - ref["logprob"]).max() <= lp_tol
     assert np.all(lp <= 0)
@@ -104,9 +125,40 @@ def test_bf16_ragged_shapes(d, V, lens, seed):
 
 
 def test_bf16_several_backward_panels():
-    """T = 150 001 spans three backward panels (at most 65 536 rows each), the last one ragged."""
+    """T = 150 001 spans three backward panels (53 248 rows each, the last one ragged); rollouts 1 and
+    4 straddle the panel boundaries at 53 248 and 106 496."""
+    lens = [50000, 9000, 40000, 233, 50768, 0]
+    b = _custom_batch("bf16", d=64, V=520, lens=lens, n_groups=2, seed=5, beta=1.0, noise=0.02)
+    res = _run(b)
+    ref = oracle_full(b)
+    _check(b, res, ref, lp_tol=2e-2, rel_tol=1e-3, g_rtol=2e-2, g_atol_frac=6e-3)
+
+
+def test_bf16_rollout_longer_than_a_panel_takes_two_passes():
+    """A 65 536-token rollout does not fit one 53 248-row panel: the device sends the call down the
+    two-pass schedule, with the same results."""
     lens = [65536, 9000, 40000, 233, 35232, 0]
     b = _custom_batch("bf16", d=64, V=520, lens=lens, n_groups=2, seed=5, beta=1.0, noise=0.02)
+    res = _run(b)
+    ref = oracle_full(b)
+    _check(b, res, ref, lp_tol=2e-2, rel_tol=1e-3, g_rtol=2e-2, g_atol_frac=6e-3, fallback=True)
+
+
+def test_bf16_logit_outside_the_sweep_range_takes_two_passes():
+    """One vocabulary row (outside the sampled first tile, never the sampled token) aligned with one
+    hidden state gives that token a logit ~300 nats above the rest: beyond what the single sweep's
+    fixed reference exponent covers, so the call falls back, and stays exact."""
+    b = _custom_batch("bf16", d=128, V=900, lens=[200, 150, 1, 161], n_groups=2, seed=14, beta=1.0)
+    b.tokens = (b.tokens % 700).to(torch.int32)                    # never token 800
+    b.W[800] = (b.H[300].float() * (300.0 / float((b.H[300].float() ** 2).sum()))).bfloat16()
+    b.logq = synth.engine_logprobs(b.H, b.W, b.tokens) + 0.1
+    res = _run(b)
+    ref = oracle_full(b)
+    assert ref["logprob"][300] < -250                               # the sampled token of that row is hopeless
+    _check(b, res, ref, lp_tol=2e-2, rel_tol=1e-3, g_rtol=2e-2, g_atol_frac=6e-3, fallback=True)
+    # ... while 60 nats above the rest is inside the range: served by the single sweep
+    b.W[800] = (b.H[300].float() * (60.0 / float((b.H[300].float() ** 2).sum()))).bfloat16()
+    b.logq = synth.engine_logprobs(b.H, b.W, b.tokens) + 0.1
     res = _run(b)
     ref = oracle_full(b)
     _check(b, res, ref, lp_tol=2e-2, rel_tol=1e-3, g_rtol=2e-2, g_atol_frac=6e-3)
@@ -338,7 +390,12 @@ def test_empty_batch_and_forward_only():
     b = _custom_batch("bf16", d=64, V=300, lens=[40, 24], n_groups=2, seed=12, beta=1.0)
     fwd = _run(b, backward=False)
     full = _run(b)
-    assert fwd.dH is None and torch.equal(fwd.loss, full.loss) and torch.equal(fwd.logprob, full.logprob)
+    assert fwd.dH is None
+    if _MODE[0] == "two_pass":      # same kernels in the same order: identical bits
+        assert torch.equal(fwd.loss, full.loss) and torch.equal(fwd.logprob, full.logprob)
+    else:                           # the single sweep sums the soft-max in another order
+        assert float((fwd.logprob - full.logprob).abs().max()) <= 2e-6
+        assert abs(fwd.loss.item() - full.loss.item()) <= 1e-5 * abs(full.loss.item())
 
 
 def test_peaked_logits_stay_finite():
