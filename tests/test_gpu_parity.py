@@ -510,3 +510,36 @@ def test_grpo_degenerate_groups_and_errors():
     with pytest.raises(oapl.OaplError):
         oapl.grpo_loss_fwd_bwd(b.H, b.W, b.tokens, logq, logp_old, b.seq_offsets, b.rewards, b.group_ids, 2,
                                clip_eps=1.5)
+
+
+def test_loss_call_replays_from_a_hip_graph():
+    """The entry point only enqueues kernels on the caller's stream (no allocation, no host wait, fill
+    kernels instead of memsets), so a call can be captured once and replayed: every replay, with eager
+    work and synchronisations in between and with changed inputs, matches the eager call bit for bit."""
+    b = _custom_batch("bf16", d=128, V=1100, lens=[300, 41, 0, 260, 7], n_groups=2, seed=40, beta=0.8)
+    dt = oapl.OAPL_BF16
+    ws = torch.empty(oapl.workspace_bytes(b.T, 128, 1100, 5, 2, dt, True), dtype=torch.uint8, device=DEV)
+    dH, dW = torch.empty_like(b.H), torch.empty(1100, 128, device=DEV)
+    logq = b.logq.clone()
+
+    def call():
+        return oapl.loss_fwd_bwd(b.H, b.W, b.tokens, logq, b.seq_offsets, b.rewards, b.group_ids, 2, b.beta,
+                                 workspace=ws, dH=dH, dW=dW)
+    call()                                   # first call outside the capture: one-time kernel attributes
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        captured = call()
+    for k in range(3):
+        logq.copy_(b.logq + 0.01 * k)        # new inputs in the captured buffers
+        eager = call()
+        want = [t.clone() for t in (eager.loss, eager.logprob, eager.seq_logratio, eager.dH, eager.dW)]
+        dH.zero_()
+        dW.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert oapl.read_device_status(ws) == 0
+        for got, ref in zip((captured.loss, captured.logprob, captured.seq_logratio, dH, dW), want):
+            assert torch.equal(got, ref), k
