@@ -22,10 +22,15 @@ constexpr double kLn2 = 0.6931471805599453094;
 // "minus infinity" that survives (m - m) without producing NaN.
 constexpr float kNegHuge = -3.0e38f;
 
-// Packed bf16 operand layout of the MFMA kernels: blocks of 256 rows x 64 k, 32 KiB each.
-constexpr int kPackRows = 256;                          // rows of a packed block
+// Packed bf16 operand layout of the MFMA kernels: a matrix is cut into blocks of R rows x 64 k
+// (R * 128 bytes, row-major inside the block), R = 256 for operands that feed the tile's m side
+// ("A": W, W^T, (f o H)^T) and R = 384 for operands that feed its n side ("B": H, G, G^T).
 constexpr int kPackK = 64;                              // k-extent of a packed block
-constexpr int kPackBlockBytes = kPackRows * kPackK * 2; // 32 KiB
+constexpr int kPackRowBytes = kPackK * 2;               // 128
+constexpr int kPackRowsA = 256;                         // = tile extent along m
+constexpr int kPackRowsB = 384;                         // = tile extent along n
+constexpr int kPackBlockBytesA = kPackRowsA * kPackRowBytes;   // 32 KiB
+constexpr int kPackBlockBytesB = kPackRowsB * kPackRowBytes;   // 48 KiB
 
 // Status words recorded by kernels; the values are those of oapl_status.
 constexpr int kErrOffsets = 4;

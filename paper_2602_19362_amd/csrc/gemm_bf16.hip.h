@@ -1,17 +1,21 @@
 // bf16 MFMA contractions of the OAPL loss head, hand-written for gfx950.
 //
-// One main loop serves all four dense steps of the path.  It computes a
-// 256 x 256 tile of  C[m][n] = sum_k A[m][k] * B[n][k]  with both operands
+// One main loop serves all dense steps of the path.  It computes a
+// 256 x 384 tile of  C[m][n] = sum_k A[m][k] * B[n][k]  with both operands
 // k-contiguous, fp32 accumulation in v_mfma_f32_32x32x16_bf16, operands
 // streamed L2 -> LDS by direct-to-LDS buffer loads (no VGPR staging) into a
-// two-stage, XOR-swizzled LDS ring, 8 wavefronts (two per SIMD, so one
-// wavefront's waits are covered by the other's MFMAs).
+// two-stage, XOR-swizzled LDS ring that fills the CU's 160 KB, 8 wavefronts
+// (two per SIMD, so one wavefront's waits are covered by the other's MFMAs),
+// each a 64 x 192 patch (192 accumulator registers per lane).  The tile is as
+// large as registers and LDS allow: operand delivery from L2 is what the loop
+// waits for, and 256 x 384 needs 17 % fewer operand bytes per flop than 256 x 256.
 //
 // Operand layout in HBM ("packed"): a matrix with R rows and K columns is
-// stored as blocks of 256 rows x 64 columns, block (rt, kt) at byte offset
-// (rt * n_kt + kt) * 32 KiB, row-major inside the block (128 B per row), zero
-// padded to whole blocks.  One k-step of one tile is then ONE contiguous 32 KiB
-// read per operand (full 128-byte lines, sequential DRAM pages), instead of 256
+// stored as blocks of RB rows x 64 columns (RB = 256 for the m-side operand,
+// 384 for the n-side operand), block (rt, kt) at byte offset
+// (rt * n_kt + kt) * RB * 128, row-major inside the block (128 B per row), zero
+// padded to whole blocks.  One k-step of one tile is then ONE contiguous 32 / 48 KiB
+// read per operand (full 128-byte lines, sequential DRAM pages), instead of
 // row fragments spread over a 2 MB .. 80 MB span, and ragged edges need no
 // special case in the loads: padding is zeros.  The caller's row-major H and W
 // are packed once per call by k_pack_rows / k_pack_transposed; the kernels
@@ -43,24 +47,31 @@ struct TileCfg {
   static constexpr int BK = kPackK;             // k-extent of one LDS stage
   static constexpr int NS = NS_;                // LDS stages in the ring
   static constexpr int KSTEPS = BK / 16;        // MFMA k-steps per stage
-  static constexpr int ROW_BYTES = BK * 2;      // 128
-  static constexpr int STAGE = kPackBlockBytes; // one operand, one stage
-  static constexpr int B_OFF = NS * STAGE;
-  static constexpr int MAIN_BYTES = 2 * NS * STAGE;
-  static constexpr int NI = kPackRows / (8 * NW);  // direct loads per wave, operand and stage (8 rows each)
-  // bf16 staging tiles used by epilogues (16 B of padding per row).
+  static constexpr int ROW_BYTES = kPackRowBytes;
+  static constexpr int STAGE_A = BM * ROW_BYTES;   // one stage of the m-side operand
+  static constexpr int STAGE_B = BN * ROW_BYTES;   // ... of the n-side operand
+  static constexpr int B_OFF = NS * STAGE_A;
+  static constexpr int MAIN_BYTES = NS * (STAGE_A + STAGE_B);
+  static constexpr int NI_A = BM / (8 * NW);    // direct loads per wave and stage (8 rows each), m-side operand
+  static constexpr int NI_B = BN / (8 * NW);    // ... n-side operand
+  // bf16 staging tiles used by epilogues (16 B of padding per row).  A whole tile does not fit
+  // the LDS, so epilogues stage it in chunks: [n][m] by wave column (BN / WN rows of n at a
+  // time), [m][n] by pairs of wave rows (BM / MN_CHUNKS rows of m at a time).
   static constexpr int PITCH_NM = BM * 2 + 16;  // tile stored [n][m]
   static constexpr int PITCH_MN = BN * 2 + 16;  // tile stored [m][n]
-  static constexpr int STAGE_NM = BN * PITCH_NM;
-  static constexpr int STAGE_MN = BM * PITCH_MN;
+  static constexpr int NM_CHUNKS = WN, NM_ROWS = BN / WN;
+  static constexpr int MN_CHUNKS = WM >= 2 ? WM / 2 : 1, MN_ROWS = BM / MN_CHUNKS;
+  static constexpr int STAGE_NM = NM_ROWS * PITCH_NM;
+  static constexpr int STAGE_MN = MN_ROWS * PITCH_MN;
   static constexpr int RED_BYTES = WM * BN * 8;
   static constexpr int LDS_BYTES =
       MAIN_BYTES > STAGE_NM ? (MAIN_BYTES > STAGE_MN ? MAIN_BYTES : STAGE_MN)
                             : (STAGE_NM > STAGE_MN ? STAGE_NM : STAGE_MN);
-  static_assert(BM == kPackRows && BN == kPackRows, "tiles are one packed block tall");
-  static_assert(NS >= 2 && NS <= 2, "ring size");
-  static_assert(kPackRows % (8 * NW) == 0, "block rows must split over waves");
+  static_assert(BM == kPackRowsA, "the m side of a tile is one packed block tall");
+  static_assert(NS == 2, "ring size");
+  static_assert(BM % (8 * NW) == 0 && BN % (8 * NW) == 0, "block rows must split over waves");
   static_assert(RED_BYTES + RED_BYTES / 2 <= LDS_BYTES, "reduction scratch must fit");
+  static_assert(LDS_BYTES <= 160 * 1024, "LDS of one CU");
 };
 
 typedef __attribute__((address_space(3))) char* lds_char_ptr;
@@ -77,7 +88,7 @@ struct Mainloop {
   static __device__ __forceinline__ int swz(int row) { return (row >> 1) & 7; }
 
   __amdgpu_buffer_rsrc_t ra, rb;
-  int voff[C::NI];                    // per-lane byte offset of this lane's chunk inside a packed block
+  int voff;                           // per-lane byte offset of this lane's chunk inside the first 8 rows a wave loads
   int rdA[C::KSTEPS], rdB[C::KSTEPS]; // LDS byte offsets of this lane's operand fragment per k-step
   int wave, lane;
 
@@ -87,12 +98,14 @@ struct Mainloop {
     wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     lane = tid & 63;
     const int wm = wave / C::WN, wn = wave % C::WN;
-#pragma unroll
-    for (int i = 0; i < C::NI; ++i) {
-      // one wave-wide load covers 8 block rows; lane l lands at LDS byte l*16 of that 1 KiB
-      const int row = (i * C::NW + wave) * 8 + (lane >> 3);
-      const int c = (lane & 7) ^ swz(row);
-      voff[i] = row * C::ROW_BYTES + c * 16;
+    // One wave-wide load covers 8 block rows; lane l lands at LDS byte l*16 of that 1 KiB.  Load i of
+    // a wave takes rows (i * NW + wave) * 8 ..: 8 * NW rows further per i, which leaves the swizzle
+    // term unchanged (8 * NW is a multiple of 16), so one lane offset serves every i and both operands;
+    // the i term goes into the scalar offset.
+    static_assert((8 * C::NW) % 16 == 0, "swizzle must repeat from one load of a wave to the next");
+    {
+      const int row = wave * 8 + (lane >> 3);
+      voff = row * C::ROW_BYTES + (((lane & 7) ^ swz(row)) << 4);
     }
     const int rowA = wm * C::TM * 32 + (lane & 31);
     const int rowB = wn * C::TN * 32 + (lane & 31);
@@ -104,26 +117,27 @@ struct Mainloop {
     }
   }
 
-  // Operand = one row-tile strip of a packed matrix: n_kt consecutive 32 KiB blocks.
+  // Operand = one row-tile strip of a packed matrix: n_kt consecutive blocks of 32 KiB (A) / 48 KiB (B).
   __device__ __forceinline__ void set_a(const bf16_t* strip, int n_kt) {
-    ra = __builtin_amdgcn_make_buffer_rsrc((void*)strip, 0, n_kt * kPackBlockBytes, 0x00020000);
+    ra = __builtin_amdgcn_make_buffer_rsrc((void*)strip, 0, n_kt * C::STAGE_A, 0x00020000);
   }
   __device__ __forceinline__ void set_b(const bf16_t* strip, int n_kt) {
-    rb = __builtin_amdgcn_make_buffer_rsrc((void*)strip, 0, n_kt * kPackBlockBytes, 0x00020000);
+    rb = __builtin_amdgcn_make_buffer_rsrc((void*)strip, 0, n_kt * C::STAGE_B, 0x00020000);
   }
 
   // Starts the direct-to-LDS loads of k-block kt into ring slot STAGE (a literal at the call sites,
   // so the LDS addresses fold to constants once inlined).
   __device__ __forceinline__ void issue(const int STAGE, lds_char_ptr smem, int kt) {
-    const int soff = kt * kPackBlockBytes;
 #pragma unroll
-    for (int i = 0; i < C::NI; ++i)
+    for (int i = 0; i < C::NI_A; ++i)
       __builtin_amdgcn_raw_ptr_buffer_load_lds(
-          ra, (lds_void_ptr)(smem + STAGE * C::STAGE + (i * C::NW + wave) * 1024), 16, voff[i], soff, 0, 0);
+          ra, (lds_void_ptr)(smem + STAGE * C::STAGE_A + (i * C::NW + wave) * 1024), 16, voff,
+          kt * C::STAGE_A + i * C::NW * 1024, 0, 0);
 #pragma unroll
-    for (int i = 0; i < C::NI; ++i)
+    for (int i = 0; i < C::NI_B; ++i)
       __builtin_amdgcn_raw_ptr_buffer_load_lds(
-          rb, (lds_void_ptr)(smem + C::B_OFF + STAGE * C::STAGE + (i * C::NW + wave) * 1024), 16, voff[i], soff, 0, 0);
+          rb, (lds_void_ptr)(smem + C::B_OFF + STAGE * C::STAGE_B + (i * C::NW + wave) * 1024), 16, voff,
+          kt * C::STAGE_B + i * C::NW * 1024, 0, 0);
   }
 
   __device__ __forceinline__ void compute(const int STAGE, lds_char_ptr smem, f32x16 (&acc)[C::TM][C::TN]) {
@@ -132,10 +146,10 @@ struct Mainloop {
       bf16x8 a[C::TM], b[C::TN];
 #pragma unroll
       for (int i = 0; i < C::TM; ++i)
-        a[i] = *(const __attribute__((address_space(3))) bf16x8*)(smem + STAGE * C::STAGE + rdA[ks] + i * 32 * C::ROW_BYTES);
+        a[i] = *(const __attribute__((address_space(3))) bf16x8*)(smem + STAGE * C::STAGE_A + rdA[ks] + i * 32 * C::ROW_BYTES);
 #pragma unroll
       for (int j = 0; j < C::TN; ++j)
-        b[j] = *(const __attribute__((address_space(3))) bf16x8*)(smem + STAGE * C::STAGE + rdB[ks] + j * 32 * C::ROW_BYTES);
+        b[j] = *(const __attribute__((address_space(3))) bf16x8*)(smem + STAGE * C::STAGE_B + rdB[ks] + j * 32 * C::ROW_BYTES);
 #pragma unroll
       for (int i = 0; i < C::TM; ++i)
 #pragma unroll
@@ -159,15 +173,20 @@ struct Mainloop {
   // previous tile (finish() ends with a barrier).
   __device__ __forceinline__ void start(lds_char_ptr smem) { issue(0, smem, 0); }
 
-  // acc += A_tile * B_tile^T over k-blocks [0, nk) after start().  Ends with a barrier: on return
-  // every wave is done reading LDS, so the caller may reuse it (or start() the next tile) at once.
-  __device__ __forceinline__ void finish(lds_char_ptr smem, int nk, f32x16 (&acc)[C::TM][C::TN]) {
-    int kt = 0;
-    for (; kt + 2 <= nk; kt += 2) {
+  // k-blocks [k0, k1) of a tile with nk k-blocks in all (k0 even, after start() or an earlier steps()).
+  __device__ __forceinline__ void steps(lds_char_ptr smem, int k0, int k1, int nk, f32x16 (&acc)[C::TM][C::TN]) {
+    int kt = k0;
+    for (; kt + 2 <= k1; kt += 2) {
       step(0, smem, kt, nk, acc);
       step(1, smem, kt + 1, nk, acc);
     }
-    if (kt < nk) step(0, smem, kt, nk, acc);
+    if (kt < k1) step(0, smem, kt, nk, acc);
+  }
+
+  // acc += A_tile * B_tile^T over k-blocks [0, nk) after start().  Ends with a barrier: on return
+  // every wave is done reading LDS, so the caller may reuse it (or start() the next tile) at once.
+  __device__ __forceinline__ void finish(lds_char_ptr smem, int nk, f32x16 (&acc)[C::TM][C::TN]) {
+    steps(smem, 0, nk, nk, acc);
     __syncthreads();
   }
 };
@@ -187,18 +206,23 @@ __device__ __forceinline__ void zero_acc(f32x16 (&acc)[C::TM][C::TN]) {
 __device__ __forceinline__ constexpr int acc_row(int i, int r) { return i * 32 + 8 * (r >> 2) + (r & 3); }
 
 // ---------------------------------------------------------------------------
-// bf16 staging of an accumulator tile through LDS for 16-byte coalesced stores
+// bf16 staging of an accumulator tile through LDS for 16-byte coalesced stores.
+// A whole tile is larger than the LDS, so it goes in chunks (see TileCfg); every
+// stage_* call must be followed by a barrier, then the matching store_*, then a
+// barrier before the next chunk is staged.
 // ---------------------------------------------------------------------------
 
-// LDS tile [n][m]: each lane writes 4 consecutive m (8 bytes) per step.
+// LDS chunk [n][m] (n = the BN / WN columns of wave column `chunk`): each lane of those waves
+// writes 4 consecutive m (8 bytes) per step.
 template <class C>
-__device__ __forceinline__ void stage_nm(lds_char_ptr smem, const f32x16 (&acc)[C::TM][C::TN]) {
+__device__ __forceinline__ void stage_nm(lds_char_ptr smem, const f32x16 (&acc)[C::TM][C::TN], int chunk) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int wm = wave / C::WN, wn = wave % C::WN;
   const int h = lane >> 5;
+  if (wn != chunk) return;
 #pragma unroll
   for (int j = 0; j < C::TN; ++j) {
-    const int n_l = wn * C::TN * 32 + j * 32 + (lane & 31);
+    const int n_l = j * 32 + (lane & 31);
 #pragma unroll
     for (int i = 0; i < C::TM; ++i)
 #pragma unroll
@@ -214,26 +238,46 @@ __device__ __forceinline__ void stage_nm(lds_char_ptr smem, const f32x16 (&acc)[
   }
 }
 
-// out[n][m] (row pitch ldo elements, pointer already at the tile origin):
+// Staged chunk -> out[n][m] (row pitch ldo elements, pointer at the tile origin):
 // rows n < n_rows, columns m < m_cols (m_cols a multiple of 8).
 template <class C>
-__device__ __forceinline__ void store_nm(lds_char_ptr smem, bf16_t* out, int64_t ldo, int64_t n_rows, int64_t m_cols) {
+__device__ __forceinline__ void store_nm(lds_char_ptr smem, bf16_t* out, int64_t ldo, int64_t n_rows, int64_t m_cols,
+                                         int chunk) {
   constexpr int CH = C::BM / 8;
-  for (int idx = threadIdx.x; idx < C::BN * CH; idx += C::NT) {
+  for (int idx = threadIdx.x; idx < C::NM_ROWS * CH; idx += C::NT) {
     const int n_l = idx / CH, ch = idx % CH;
-    if (n_l < n_rows && ch * 8 < m_cols) {
+    const int n = chunk * C::NM_ROWS + n_l;
+    if (n < n_rows && ch * 8 < m_cols) {
       const u32x4 v = *(const __attribute__((address_space(3))) u32x4*)(smem + n_l * C::PITCH_NM + ch * 16);
-      *(u32x4*)(out + (int64_t)n_l * ldo + ch * 8) = v;
+      *(u32x4*)(out + (int64_t)n * ldo + ch * 8) = v;
     }
   }
 }
 
-// LDS tile [m][n]: 2-byte writes, consecutive lanes write consecutive n.
+// Staged chunk [n][m] -> packed n-side matrix whose rows are the n index and whose k index is m:
+// `strip` is block (n-tile, 0) of the destination, kb0 the first k-block (m0 / 64).  Whole rows are
+// written (the packed buffers are padded to whole tiles; padding must be zeros).
 template <class C>
-__device__ __forceinline__ void stage_mn(lds_char_ptr smem, const f32x16 (&acc)[C::TM][C::TN]) {
+__device__ __forceinline__ void store_nm_packed(lds_char_ptr smem, bf16_t* strip, int kb0, int chunk) {
+  constexpr int CH = C::BM / 8;
+  char* dst = (char*)strip + (int64_t)kb0 * C::STAGE_B;
+  for (int idx = threadIdx.x; idx < C::NM_ROWS * CH; idx += C::NT) {
+    const int n_l = idx / CH, ch = idx % CH;
+    const int n = chunk * C::NM_ROWS + n_l;
+    const u32x4 v = *(const __attribute__((address_space(3))) u32x4*)(smem + n_l * C::PITCH_NM + ch * 16);
+    *(u32x4*)(dst + (ch >> 3) * C::STAGE_B + n * kPackRowBytes + (ch & 7) * 16) = v;
+  }
+}
+
+// LDS chunk [m][n] (m = the BM / MN_CHUNKS rows of wave rows chunk * WM / MN_CHUNKS ...): 2-byte
+// writes, consecutive lanes write consecutive n.
+template <class C>
+__device__ __forceinline__ void stage_mn(lds_char_ptr smem, const f32x16 (&acc)[C::TM][C::TN], int chunk) {
+  constexpr int WPC = C::WM / C::MN_CHUNKS;   // wave rows per chunk
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int wm = wave / C::WN, wn = wave % C::WN;
   const int h = lane >> 5;
+  if (wm / WPC != chunk) return;
 #pragma unroll
   for (int j = 0; j < C::TN; ++j) {
     const int n_l = wn * C::TN * 32 + j * 32 + (lane & 31);
@@ -241,35 +285,102 @@ __device__ __forceinline__ void stage_mn(lds_char_ptr smem, const f32x16 (&acc)[
     for (int i = 0; i < C::TM; ++i)
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        const int m_l = wm * C::TM * 32 + acc_row(i, r) + 4 * h;
+        const int m_l = (wm % WPC) * C::TM * 32 + acc_row(i, r) + 4 * h;
         *(__attribute__((address_space(3))) bf16_t*)(smem + m_l * C::PITCH_MN + n_l * 2) = (bf16_t)acc[i][j][r];
       }
   }
 }
 
-// Staged [n][m] tile -> packed matrix whose rows are the n index and whose k index is m:
-// `strip` is block (n-tile, 0) of the destination, kb0 the first k-block (m0 / 64).  The whole
-// tile is written (the packed buffers are padded to whole tiles; padding must be zeros).
+// Staged chunk [m][n] -> packed n-side matrix whose rows are the m index (global row m0 + ...,
+// blocks of BN rows) and whose k index is n: `base` is the destination matrix, n_kt its strip
+// pitch in k-blocks, kb0 the first k-block (n0 / 64).
 template <class C>
-__device__ __forceinline__ void store_nm_packed(lds_char_ptr smem, bf16_t* strip, int kb0) {
-  constexpr int CH = C::BM / 8;
-  char* dst = (char*)strip + (int64_t)kb0 * kPackBlockBytes;
-  for (int idx = threadIdx.x; idx < C::BN * CH; idx += C::NT) {
-    const int n_l = idx / CH, ch = idx % CH;
-    const u32x4 v = *(const __attribute__((address_space(3))) u32x4*)(smem + n_l * C::PITCH_NM + ch * 16);
-    *(u32x4*)(dst + (ch >> 3) * kPackBlockBytes + n_l * 128 + (ch & 7) * 16) = v;
+__device__ __forceinline__ void store_mn_packed(lds_char_ptr smem, bf16_t* base, int n_kt, int m0, int kb0, int chunk) {
+  constexpr int CH = C::BN / 8;
+  for (int idx = threadIdx.x; idx < C::MN_ROWS * CH; idx += C::NT) {
+    const int m_l = idx / CH, ch = idx % CH;
+    const int m = m0 + chunk * C::MN_ROWS + m_l;
+    const int blk = m / C::BN, r = m - blk * C::BN;
+    const u32x4 v = *(const __attribute__((address_space(3))) u32x4*)(smem + m_l * C::PITCH_MN + ch * 16);
+    char* dst = (char*)base + ((int64_t)blk * n_kt + kb0 + (ch >> 3)) * C::STAGE_B;
+    *(u32x4*)(dst + r * kPackRowBytes + (ch & 7) * 16) = v;
   }
 }
 
-// Staged [m][n] tile -> packed matrix whose rows are the m index and whose k index is n.
+// Both packed copies of a finished tile: rows = n (tokens) with k = m, and rows = m with k = n.
 template <class C>
-__device__ __forceinline__ void store_mn_packed(lds_char_ptr smem, bf16_t* strip, int kb0) {
-  constexpr int CH = C::BN / 8;
-  char* dst = (char*)strip + (int64_t)kb0 * kPackBlockBytes;
-  for (int idx = threadIdx.x; idx < C::BM * CH; idx += C::NT) {
-    const int m_l = idx / CH, ch = idx % CH;
-    const u32x4 v = *(const __attribute__((address_space(3))) u32x4*)(smem + m_l * C::PITCH_MN + ch * 16);
-    *(u32x4*)(dst + (ch >> 3) * kPackBlockBytes + m_l * 128 + (ch & 7) * 16) = v;
+__device__ __forceinline__ void store_tile_both_ways(lds_char_ptr smem, const f32x16 (&acc)[C::TM][C::TN],
+                                                     bf16_t* Gp_strip, int m0, bf16_t* GTp, int gt_n_kt, int64_t n0) {
+#pragma unroll 1
+  for (int c = 0; c < C::NM_CHUNKS; ++c) {
+    stage_nm<C>(smem, acc, c);
+    __syncthreads();
+    store_nm_packed<C>(smem, Gp_strip, m0 / kPackK, c);
+    __syncthreads();
+  }
+#pragma unroll 1
+  for (int c = 0; c < C::MN_CHUNKS; ++c) {
+    stage_mn<C>(smem, acc, c);
+    __syncthreads();
+    store_mn_packed<C>(smem, GTp, gt_n_kt, m0, (int)(n0 / kPackK), c);
+    __syncthreads();
+  }
+}
+
+// ---------------------------------------------------------------------------
+// The same two packed copies from a tile already rounded to bf16 pairs:
+// pk[i][j][p] holds rows acc_row(i, 2p) and acc_row(i, 2p) + 1 (low / high half) of column j.
+// Half the registers of the fp32 tile, so nothing spills around the stores.
+// ---------------------------------------------------------------------------
+
+// Copy with rows = n, k = m, straight from registers: a lane owns 4 consecutive m (8 bytes) of its
+// row n per (i, q), the two lane halves own adjacent 8 bytes, and a wave row covers whole 128-byte
+// rows of a k-block, which the L2 merges into full lines.  `strip` is block (n-tile, 0) of the
+// destination, kb0 the first k-block (m0 / 64).
+template <class C>
+__device__ __forceinline__ void store_nm_packed_direct(const uint32_t (&pk)[C::TM][C::TN][8], bf16_t* strip, int kb0) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int wm = wave / C::WN, wn = wave % C::WN;
+  const int h = lane >> 5;
+#pragma unroll
+  for (int j = 0; j < C::TN; ++j) {
+    const int n_l = wn * C::TN * 32 + j * 32 + (lane & 31);
+#pragma unroll
+    for (int i = 0; i < C::TM; ++i) {
+      const int m_blk = wm * C::TM * 32 + i * 32;              // multiple of 32: k-block m_blk / 64, half m_blk % 64
+      char* dst = (char*)strip + (int64_t)(kb0 + m_blk / kPackK) * C::STAGE_B + n_l * kPackRowBytes +
+                  ((m_blk % kPackK) + 4 * h) * 2;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) *(u32x2*)(dst + 16 * q) = u32x2{pk[i][j][2 * q], pk[i][j][2 * q + 1]};
+    }
+  }
+}
+
+// LDS chunk [m][n] from the packed pairs.  Neighbouring lanes (columns n, n + 1) swap halves so
+// that each lane writes 4 bytes: the even lane row m (its own low half, the neighbour's low half),
+// the odd lane row m + 1 (the neighbour's high half, its own high half).
+template <class C>
+__device__ __forceinline__ void stage_mn_pk(lds_char_ptr smem, const uint32_t (&pk)[C::TM][C::TN][8], int chunk) {
+  constexpr int WPC = C::WM / C::MN_CHUNKS;   // wave rows per chunk
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int wm = wave / C::WN, wn = wave % C::WN;
+  const int h = lane >> 5, odd = lane & 1;
+  if (wm / WPC != chunk) return;
+  // v_perm_b32 picks bytes from {neighbour (4..7), own (0..3)}
+  const uint32_t sel = odd ? 0x03020706u : 0x05040100u;
+#pragma unroll
+  for (int j = 0; j < C::TN; ++j) {
+    const int n_l = wn * C::TN * 32 + j * 32 + (lane & 31) - odd;
+#pragma unroll
+    for (int i = 0; i < C::TM; ++i)
+#pragma unroll
+      for (int p = 0; p < 8; ++p) {
+        const uint32_t own = pk[i][j][p];
+        const uint32_t nbr = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)own, 0xB1 /* quad_perm 1,0,3,2 */, 0xF, 0xF, true);
+        const uint32_t w = __builtin_amdgcn_perm(nbr, own, sel);
+        const int m_l = (wm % WPC) * C::TM * 32 + acc_row(i, 2 * p) + 4 * h + odd;
+        *(__attribute__((address_space(3))) uint32_t*)(smem + m_l * C::PITCH_MN + n_l * 2) = w;
+      }
   }
 }
 
@@ -316,11 +427,11 @@ k_fwd_lse(const bf16_t* __restrict__ Wp, const bf16_t* __restrict__ Hp, int V, i
   const int mt_begin = (int)((int64_t)split * MT / n_splits);
   const int mt_end = (int)((int64_t)(split + 1) * MT / n_splits);
   const int64_t n0 = (int64_t)nt * C::BN;
-  const int64_t strip_elems = (int64_t)n_kt * (kPackBlockBytes / 2);
+  const int64_t strip_a = (int64_t)n_kt * (C::STAGE_A / 2), strip_b = (int64_t)n_kt * (C::STAGE_B / 2);
 
   Mainloop<C> ml;
   ml.setup();
-  ml.set_b(Hp + nt * strip_elems, n_kt);
+  ml.set_b(Hp + nt * strip_b, n_kt);
 
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int wm = wave / C::WN, wn = wave % C::WN;
@@ -332,7 +443,7 @@ k_fwd_lse(const bf16_t* __restrict__ Wp, const bf16_t* __restrict__ Hp, int V, i
 
   f32x16 acc[C::TM][C::TN];
   if (mt_begin < mt_end) {
-    ml.set_a(Wp + mt_begin * strip_elems, n_kt);
+    ml.set_a(Wp + mt_begin * strip_a, n_kt);
     ml.start(smem);
   }
   for (int mt = mt_begin; mt < mt_end; ++mt) {
@@ -340,7 +451,7 @@ k_fwd_lse(const bf16_t* __restrict__ Wp, const bf16_t* __restrict__ Hp, int V, i
     zero_acc<C>(acc);
     ml.finish(smem, n_kt, acc);
     if (mt + 1 < mt_end) {  // the epilogue below works in registers only: overlap it with the next tile's first loads
-      ml.set_a(Wp + (mt + 1) * strip_elems, n_kt);
+      ml.set_a(Wp + (mt + 1) * strip_a, n_kt);
       ml.start(smem);
     }
 
@@ -448,11 +559,11 @@ k_fwd_sample(const bf16_t* __restrict__ Wp, const bf16_t* __restrict__ Hp, int V
   const int mt_begin = (int)((int64_t)split * MT / n_splits);
   const int mt_end = (int)((int64_t)(split + 1) * MT / n_splits);
   const int64_t n0 = (int64_t)nt * C::BN;
-  const int64_t strip_elems = (int64_t)n_kt * (kPackBlockBytes / 2);
+  const int64_t strip_a = (int64_t)n_kt * (C::STAGE_A / 2), strip_b = (int64_t)n_kt * (C::STAGE_B / 2);
 
   Mainloop<C> ml;
   ml.setup();
-  ml.set_b(Hp + nt * strip_elems, n_kt);
+  ml.set_b(Hp + nt * strip_b, n_kt);
 
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int wm = wave / C::WN, wn = wave % C::WN;
@@ -465,7 +576,7 @@ k_fwd_sample(const bf16_t* __restrict__ Wp, const bf16_t* __restrict__ Hp, int V
 
   f32x16 acc[C::TM][C::TN];
   if (mt_begin < mt_end) {
-    ml.set_a(Wp + mt_begin * strip_elems, n_kt);
+    ml.set_a(Wp + mt_begin * strip_a, n_kt);
     ml.start(smem);
   }
   for (int mt = mt_begin; mt < mt_end; ++mt) {
@@ -473,7 +584,7 @@ k_fwd_sample(const bf16_t* __restrict__ Wp, const bf16_t* __restrict__ Hp, int V
     zero_acc<C>(acc);
     ml.finish(smem, n_kt, acc);
     if (mt + 1 < mt_end) {
-      ml.set_a(Wp + (mt + 1) * strip_elems, n_kt);
+      ml.set_a(Wp + (mt + 1) * strip_a, n_kt);
       ml.start(smem);
     }
     const int row0 = m0 + wm * C::TM * 32 + 4 * h;
@@ -558,12 +669,12 @@ k_bwd_dz(const bf16_t* __restrict__ Wp, const bf16_t* __restrict__ Hp_panel, int
   strip_tile<8>(L, MT, NTl, mt, nt);
   const int m0 = mt * C::BM;
   const int64_t n0 = (int64_t)nt * C::BN;
-  const int64_t strip_elems = (int64_t)n_kt * (kPackBlockBytes / 2);
+  const int64_t strip_a = (int64_t)n_kt * (C::STAGE_A / 2), strip_b = (int64_t)n_kt * (C::STAGE_B / 2);
 
   Mainloop<C> ml;
   ml.setup();
-  ml.set_a(Wp + mt * strip_elems, n_kt);
-  ml.set_b(Hp_panel + nt * strip_elems, n_kt);
+  ml.set_a(Wp + mt * strip_a, n_kt);
+  ml.set_b(Hp_panel + nt * strip_b, n_kt);
 
   f32x16 acc[C::TM][C::TN];
   zero_acc<C>(acc);
@@ -621,15 +732,8 @@ k_bwd_dz(const bf16_t* __restrict__ Wp, const bf16_t* __restrict__ Hp_panel, int
         }
   }
 
-  // Gp: rows = tokens (n), k = vocabulary (m)
-  stage_nm<C>(smem, acc);
-  __syncthreads();
-  store_nm_packed<C>(smem, Gp + (int64_t)nt * g_n_kt * (kPackBlockBytes / 2), m0 / kPackK);
-  __syncthreads();
-  // GTp: rows = vocabulary (m), k = tokens (n)
-  stage_mn<C>(smem, acc);
-  __syncthreads();
-  store_mn_packed<C>(smem, GTp + (int64_t)mt * gt_n_kt * (kPackBlockBytes / 2), (int)(n0 / kPackK));
+  // Gp: rows = tokens (n), k = vocabulary (m);  GTp: rows = vocabulary (m), k = tokens (n)
+  store_tile_both_ways<C>(smem, acc, Gp + (int64_t)nt * g_n_kt * (C::STAGE_B / 2), m0, GTp, gt_n_kt, n0);
 }
 
 // ---------------------------------------------------------------------------
@@ -668,22 +772,34 @@ k_sweep(const bf16_t* __restrict__ Wp, const bf16_t* __restrict__ Hp_panel, int 
   strip_tile<8>(L, MT, NTl, mt, nt);
   const int m0 = mt * C::BM;
   const int64_t n0 = (int64_t)nt * C::BN;
-  const int64_t strip_elems = (int64_t)n_kt * (kPackBlockBytes / 2);
+  const int64_t strip_a = (int64_t)n_kt * (C::STAGE_A / 2), strip_b = (int64_t)n_kt * (C::STAGE_B / 2);
 
   Mainloop<C> ml;
   ml.setup();
-  ml.set_a(Wp + mt * strip_elems, n_kt);
-  ml.set_b(Hp_panel + nt * strip_elems, n_kt);
-
-  f32x16 acc[C::TM][C::TN];
-  zero_acc<C>(acc);
-  ml.start(smem);
-  ml.finish(smem, n_kt, acc);
+  ml.set_a(Wp + mt * strip_a, n_kt);
+  ml.set_b(Hp_panel + nt * strip_b, n_kt);
 
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int wm = wave / C::WN, wn = wave % C::WN;
   const int h = lane >> 5;
   const int row0 = m0 + wm * C::TM * 32 + 4 * h;   // first vocabulary row of this lane
+
+  f32x16 acc[C::TM][C::TN];
+  zero_acc<C>(acc);
+  ml.start(smem);
+  // the epilogue's per-token references are requested two k-blocks before the end, so that their
+  // latency hides behind the last multiplications instead of stalling the epilogue
+  const int k_early = n_kt > 2 ? (n_kt - 2) & ~1 : 0;
+  ml.steps(smem, 0, k_early, n_kt, acc);
+  float r2v[C::TN];
+#pragma unroll
+  for (int j = 0; j < C::TN; ++j) {
+    const int64_t n = n0 + wn * C::TN * 32 + j * 32 + (lane & 31);
+    // token columns past the panel: reference +inf, every entry 2^(-inf) = 0
+    r2v[j] = n < n_valid ? ref2[n] : __builtin_inff();
+  }
+  ml.steps(smem, k_early, n_kt, n_kt, acc);
+  __syncthreads();
 
   if (m0 + C::BM > V) {  // ragged last vocabulary tile: rows >= V do not exist (2^(-inf) = 0 below)
 #pragma unroll
@@ -696,23 +812,27 @@ k_sweep(const bf16_t* __restrict__ Wp, const bf16_t* __restrict__ Hp_panel, int 
         }
   }
   float csum[C::TN];
+  uint32_t pk[C::TM][C::TN][8];   // the tile as bf16 pairs: rows acc_row(i, 2p), +1
 #pragma unroll
   for (int j = 0; j < C::TN; ++j) {
-    const int64_t n = n0 + wn * C::TN * 32 + j * 32 + (lane & 31);
-    // token columns past the panel: reference +inf, every entry 2^(-inf) = 0
-    const float r2 = n < n_valid ? ref2[n] : __builtin_inff();
+    const float r2 = r2v[j];
     float sum = 0.f;
 #pragma unroll
     for (int i = 0; i < C::TM; ++i)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const float e = __builtin_amdgcn_exp2f(__builtin_fmaf(acc[i][j][r], kLog2e, -r2));
-        acc[i][j][r] = e;
-        sum += e;
+      for (int p = 0; p < 8; ++p) {
+        const float e0 = __builtin_amdgcn_exp2f(__builtin_fmaf(acc[i][j][2 * p], kLog2e, -r2));
+        const float e1 = __builtin_amdgcn_exp2f(__builtin_fmaf(acc[i][j][2 * p + 1], kLog2e, -r2));
+        sum += e0;
+        sum += e1;
+        const bf16x2 v = {(bf16_t)e0, (bf16_t)e1};
+        pk[i][j][p] = __builtin_bit_cast(uint32_t, v);
       }
     csum[j] = sum + __shfl_xor(sum, 32, 64);     // the two lane halves hold the same token
   }
-  // the WM waves stacked along the vocabulary, through LDS, in a fixed order
+  // Gp: rows = tokens (n), k = vocabulary (m), straight from the registers
+  store_nm_packed_direct<C>(pk, Gp + (int64_t)nt * g_n_kt * (C::STAGE_B / 2), m0 / kPackK);
+  // row sums: the WM waves stacked along the vocabulary, through LDS, in a fixed order
   __attribute__((address_space(3))) float* red = (__attribute__((address_space(3))) float*)smem;
   if (h == 0) {
 #pragma unroll
@@ -728,14 +848,14 @@ k_sweep(const bf16_t* __restrict__ Wp, const bf16_t* __restrict__ Hp_panel, int 
     }
   }
   __syncthreads();
-
-  stage_nm<C>(smem, acc);
-  __syncthreads();
-  store_nm_packed<C>(smem, Gp + (int64_t)nt * g_n_kt * (kPackBlockBytes / 2), m0 / kPackK);
-  __syncthreads();
-  stage_mn<C>(smem, acc);
-  __syncthreads();
-  store_mn_packed<C>(smem, GTp + (int64_t)mt * gt_n_kt * (kPackBlockBytes / 2), (int)(n0 / kPackK));
+  // GTp: rows = vocabulary (m), k = tokens (n), through LDS in chunks of wave rows
+#pragma unroll 1
+  for (int c = 0; c < C::MN_CHUNKS; ++c) {
+    stage_mn_pk<C>(smem, pk, c);
+    __syncthreads();
+    store_mn_packed<C>(smem, GTp, gt_n_kt, m0, (int)(n0 / kPackK), c);
+    __syncthreads();
+  }
 }
 
 // ---------------------------------------------------------------------------
@@ -764,8 +884,8 @@ k_bwd_dh(const bf16_t* __restrict__ WTp, int wt_n_kt, const bf16_t* __restrict__
 
   Mainloop<C> ml;
   ml.setup();
-  ml.set_a(WTp + (int64_t)mt * wt_n_kt * (kPackBlockBytes / 2), wt_n_kt);
-  ml.set_b(Gp + (int64_t)nt * g_n_kt * (kPackBlockBytes / 2), g_n_kt);
+  ml.set_a(WTp + (int64_t)mt * wt_n_kt * (C::STAGE_A / 2), wt_n_kt);
+  ml.set_b(Gp + (int64_t)nt * g_n_kt * (C::STAGE_B / 2), g_n_kt);
 
   f32x16 acc[C::TM][C::TN];
   zero_acc<C>(acc);
@@ -782,9 +902,13 @@ k_bwd_dh(const bf16_t* __restrict__ WTp, int wt_n_kt, const bf16_t* __restrict__
       for (int i = 0; i < C::TM; ++i) acc[i][j] *= f;
     }
   }
-  stage_nm<C>(smem, acc);
-  __syncthreads();
-  store_nm<C>(smem, dH + n0 * d + m0, d, n_valid - n0, (int64_t)d - m0);
+#pragma unroll 1
+  for (int c = 0; c < C::NM_CHUNKS; ++c) {
+    stage_nm<C>(smem, acc, c);
+    __syncthreads();
+    store_nm<C>(smem, dH + n0 * d + m0, d, n_valid - n0, (int64_t)d - m0, c);
+    __syncthreads();
+  }
 }
 
 // ---------------------------------------------------------------------------
@@ -813,8 +937,8 @@ k_bwd_dw(const bf16_t* __restrict__ HTp, const bf16_t* __restrict__ GTp, int t_n
 
   Mainloop<C> ml;
   ml.setup();
-  ml.set_a(HTp + (int64_t)mt * t_n_kt * (kPackBlockBytes / 2), t_n_kt);
-  ml.set_b(GTp + (int64_t)nt * t_n_kt * (kPackBlockBytes / 2), t_n_kt);
+  ml.set_a(HTp + (int64_t)mt * t_n_kt * (C::STAGE_A / 2), t_n_kt);
+  ml.set_b(GTp + (int64_t)nt * t_n_kt * (C::STAGE_B / 2), t_n_kt);
 
   f32x16 acc[C::TM][C::TN];
   zero_acc<C>(acc);
@@ -852,19 +976,17 @@ k_bwd_dw(const bf16_t* __restrict__ HTp, const bf16_t* __restrict__ GTp, int t_n
 // Packing of row-major matrices into the block layout the main loop reads.
 // ---------------------------------------------------------------------------
 
-// dst = packed(src), src [R, K] row-major with leading dimension ld (K and ld multiples of 8).
-// One workgroup per 256 x 64 block; blocks in [0, n_rt) x [0, n_kt); everything outside
-// [0, R) x [0, K) is written as zero.
+// dst = packed(src), src [R, K] row-major with leading dimension ld (K and ld multiples of 8),
+// in blocks of `rb` rows (256 for an m-side operand, 384 for an n-side operand).  One workgroup
+// per block; blocks in [0, n_rt) x [0, n_kt); everything outside [0, R) x [0, K) is written as zero.
 __global__ void __launch_bounds__(256)
-k_pack_rows(const bf16_t* __restrict__ src, int64_t R, int K, int64_t ld, bf16_t* __restrict__ dst, int n_kt) {
+k_pack_rows(const bf16_t* __restrict__ src, int64_t R, int K, int64_t ld, bf16_t* __restrict__ dst, int n_kt, int rb) {
   const int kt = blockIdx.x;
   const int64_t rt = blockIdx.y;
-  char* out = (char*)dst + (rt * n_kt + kt) * (int64_t)kPackBlockBytes;
-#pragma unroll
-  for (int it = 0; it < 8; ++it) {
-    const int idx = it * 256 + threadIdx.x;       // 2048 chunks of 16 B
+  char* out = (char*)dst + (rt * n_kt + kt) * (int64_t)rb * kPackRowBytes;
+  for (int idx = threadIdx.x; idx < rb * 8; idx += 256) {   // chunks of 16 B
     const int row = idx >> 3, c = idx & 7;
-    const int64_t r = rt * kPackRows + row;
+    const int64_t r = rt * rb + row;
     const int k = kt * kPackK + c * 8;
     u32x4 v = {0u, 0u, 0u, 0u};
     if (r < R && k < K) v = *(const u32x4*)(src + r * ld + k);
@@ -872,18 +994,18 @@ k_pack_rows(const bf16_t* __restrict__ src, int64_t R, int K, int64_t ld, bf16_t
   }
 }
 
-// dst = packed(S^T) where S [R, Ccols] is row-major (ld) and optionally row-scaled:
+// dst = packed(S^T), an m-side operand (256-row blocks), where S [R, Ccols] is row-major (ld) and optionally row-scaled:
 // dst row j (a column of S), k index r (a row of S): dst(j, r) = bf16(S[r][j] * scale[r]).
 // One workgroup per destination block (jt, kt): it reads S[kt*64 .. +64][jt*256 .. +256]
 // through LDS.  Blocks in [0, n_jt) x [0, n_kt); zero outside [0, Ccols) x [0, R).
 __global__ void __launch_bounds__(256)
 k_pack_transposed(const bf16_t* __restrict__ src, int64_t R, int Ccols, int64_t ld, const float* __restrict__ scale,
                   bf16_t* __restrict__ dst, int n_kt, Gate gate) {
-  __shared__ bf16_t tile[64][kPackRows + 2];
+  __shared__ bf16_t tile[64][kPackRowsA + 2];
   if (gate_closed(gate)) return;
   const int kt = blockIdx.x, jt = blockIdx.y;
   const int64_t r0 = (int64_t)kt * kPackK;
-  const int j0 = jt * kPackRows;
+  const int j0 = jt * kPackRowsA;
   for (int i = threadIdx.x >> 6; i < 64; i += 4) {          // 4 source rows per pass, 64 lanes x 4 columns each
     const int64_t r = r0 + i;
     const float sc = (scale != nullptr && r < R) ? scale[r] : 1.f;
@@ -900,7 +1022,7 @@ k_pack_transposed(const bf16_t* __restrict__ src, int64_t R, int Ccols, int64_t 
     }
   }
   __syncthreads();
-  char* out = (char*)dst + ((int64_t)jt * n_kt + kt) * (int64_t)kPackBlockBytes;
+  char* out = (char*)dst + ((int64_t)jt * n_kt + kt) * (int64_t)kPackBlockBytesA;
 #pragma unroll
   for (int it = 0; it < 8; ++it) {
     const int idx = it * 256 + threadIdx.x;

@@ -14,12 +14,18 @@
 
 namespace oapl {
 
-// 256 x 256 x 64 tiles, 8 wavefronts in a 4 x 2 grid, each a 64 x 128 patch
-// (2 x 4 MFMA blocks, 128 accumulator registers per lane), two wavefronts per
-// SIMD; operands in a ring of 2 LDS stages (128 KB).
-typedef TileCfg<4, 2, 2, 4, 2> Cfg;
+// 256 x 384 x 64 tiles, 8 wavefronts in a 4 x 2 grid, each a 64 x 192 patch
+// (2 x 6 MFMA blocks, 192 accumulator registers per lane), two wavefronts per
+// SIMD; operands in a ring of 2 LDS stages (160 KB, the whole LDS of a CU).
+typedef TileCfg<4, 2, 2, 6, 2> Cfg;
+static_assert(Cfg::BN == kPackRowsB, "n-side operands of the loss path are packed in blocks of one tile");
+// The sampling kernel carries a running (score, index) pair per column through the main loop and
+// draws Philox blocks in its epilogue: it keeps the 256 x 256 tile (128 accumulators per lane),
+// with H packed in 256-row blocks for it.
+typedef TileCfg<4, 2, 2, 4, 2> CfgSample;
 
-constexpr int64_t kPanelBf16 = 65536;  // most token rows per backward panel (bf16 path)
+constexpr int64_t kPanelBf16 = 61440;  // most token rows per backward panel (bf16 path): 160 token tiles
+constexpr int64_t kPanelUnit = 6144;   // 16 token tiles: whole rounds of workgroups in the dH contraction at d = 4096
 constexpr int64_t kPanelF32 = 4096;    // ... (fp32 path)
 constexpr int kStatusWords = 64;       // 256-byte header
 constexpr int kNumCU = 256;            // MI355X compute units (one 128 KB-LDS workgroup each)
@@ -31,10 +37,12 @@ struct Plan {
   int d = 0, V = 0, n_seq = 0, n_groups = 0, dtype = 0;
   bool bwd = false;
   int n_parts = 0;     // soft-max partials per token
+  int n_parts_s = 0;   // (score, index) partials per token of the sampling kernel
   int64_t Tp = 0;      // rows of one backward panel
   // packed-operand geometry (bf16 path): row tiles and k-blocks (strip pitches)
   int n_rt_v = 0, n_rt_d = 0, n_kt_d = 0, n_kt_v = 0, n_kt_g = 0, n_kt_t = 0;
-  int64_t n_rt_T = 0;
+  int n_rb_v = 0;      // 384-row blocks of a matrix whose rows are the vocabulary (G^T)
+  int64_t n_rt_T = 0;  // 384-row token tiles of the whole batch
   size_t off_status = 0, off_partials = 0, off_upart = 0, off_zy = 0, off_lse2 = 0, off_diff = 0, off_coef = 0, off_delta = 0,
          off_cseq = 0, off_vstar = 0, off_gw = 0, off_omp = 0, off_inv = 0, off_Wp = 0, off_Hp = 0, off_WTp = 0, off_HTp = 0,
          off_G = 0, off_GT = 0, off_ref2 = 0, off_spart = 0, off_G2 = 0, off_GT2 = 0, total = 0;
@@ -58,44 +66,49 @@ static bool make_plan(Plan& p, int64_t T, int d, int V, int n_seq, int n_groups,
   if (dtype == OAPL_BF16) {
     const int64_t n_tiles = (T + Cfg::BN - 1) / Cfg::BN;
     const int MT = (V + Cfg::BM - 1) / Cfg::BM;
-    // Vocabulary splits of the forward kernel: one workgroup per (token tile, split), one
+    // Vocabulary splits of the streaming kernels: one workgroup per (token tile, split), one
     // workgroup per CU at a time.  Pick the split count that wastes the least of the last round
     // of workgroups and of the uneven division of vocabulary tiles, with at least ~8 tiles each.
-    const int64_t max_splits = MT / 8 > 1 ? (MT / 8 < 64 ? MT / 8 : 64) : 1;
-    int64_t splits = 1;
-    double best = -1.0;
-    for (int64_t c = 1; c <= max_splits && n_tiles > 0; ++c) {
-      const int64_t wgs = n_tiles * c;
-      const double rounds = (double)wgs / kNumCU;
-      const double fill = rounds / (double)((wgs + kNumCU - 1) / kNumCU);      // occupancy of the last round
-      const double even = ((double)MT / c) / (double)((MT + c - 1) / c);       // equal work per workgroup
-      const double score = fill * even;
-      if (score > best + 1e-9) { best = score; splits = c; }
-    }
-    p.n_parts = (int)splits;
+    auto pick_splits = [&](int64_t tiles) {
+      const int64_t max_splits = MT / 8 > 1 ? (MT / 8 < 64 ? MT / 8 : 64) : 1;
+      int64_t splits = 1;
+      double best = -1.0;
+      for (int64_t c = 1; c <= max_splits && tiles > 0; ++c) {
+        const int64_t wgs = tiles * c;
+        const double rounds = (double)wgs / kNumCU;
+        const double fill = rounds / (double)((wgs + kNumCU - 1) / kNumCU);      // occupancy of the last round
+        const double even = ((double)MT / c) / (double)((MT + c - 1) / c);       // equal work per workgroup
+        const double score = fill * even;
+        if (score > best + 1e-9) { best = score; splits = c; }
+      }
+      return (int)splits;
+    };
+    p.n_parts = pick_splits(n_tiles);
+    p.n_parts_s = pick_splits((T + CfgSample::BN - 1) / CfgSample::BN);
     // equal panels of at most kPanelBf16 rows (a short last panel would waste a whole pass
     // of the fp32 read-add-write over dW)
     const int64_t n_panels = T > 0 ? (T + kPanelBf16 - 1) / kPanelBf16 : 1;
-    // with several panels, a panel of a multiple of 4096 rows gives the dH contraction (d / 256 x
-    // Tp / 256 tiles) whole rounds of kNumCU workgroups when d is a multiple of 4096
-    p.Tp = round_up(T > 0 ? (T + n_panels - 1) / n_panels : 1, n_panels > 1 ? 4096 : Cfg::BN);
+    // with several panels, a panel of a multiple of 6144 rows gives the dH contraction (d / 256 x
+    // Tp / 384 tiles) whole rounds of kNumCU workgroups when d is a multiple of 4096
+    p.Tp = round_up(T > 0 ? (T + n_panels - 1) / n_panels : 1, n_panels > 1 ? kPanelUnit : Cfg::BN);
     if (p.Tp > kPanelBf16) p.Tp = kPanelBf16;
     p.n_rt_v = MT;
-    p.n_rt_d = (d + kPackRows - 1) / kPackRows;
+    p.n_rb_v = (int)(round_up((int64_t)MT * Cfg::BM, Cfg::BN) / Cfg::BN);
+    p.n_rt_d = (d + Cfg::BM - 1) / Cfg::BM;
     p.n_rt_T = n_tiles > 0 ? n_tiles : 1;
     p.n_kt_d = (d + kPackK - 1) / kPackK;
     p.n_kt_v = (V + kPackK - 1) / kPackK;            // W^T strips: exactly the k-blocks the dH contraction walks
-    p.n_kt_g = MT * (kPackRows / kPackK);            // G strips: whole vocabulary tiles
+    p.n_kt_g = MT * (Cfg::BM / kPackK);              // G strips: whole vocabulary tiles
     p.n_kt_t = (int)(p.Tp / kPackK);                 // strips whose k index is the panel token
   } else {
-    p.n_parts = (V + 63) / 64;
+    p.n_parts = p.n_parts_s = (V + 63) / 64;
     p.Tp = T < kPanelF32 ? (T > 0 ? T : 1) : kPanelF32;
   }
   size_t o = 0;
   auto take = [&](size_t bytes) { size_t at = o; o += (bytes + 255) / 256 * 256; return at; };
   const size_t Tn = (size_t)(T > 0 ? T : 1);
   p.off_status = take(kStatusWords * 4);
-  p.off_partials = take(Tn * (size_t)p.n_parts * 8);
+  p.off_partials = take(Tn * (size_t)(p.n_parts > p.n_parts_s ? p.n_parts : p.n_parts_s) * 8);
   p.off_upart = take(Tn * (size_t)p.n_parts * 4);
   p.off_zy = take(Tn * 4);
   p.off_lse2 = take(Tn * 4);
@@ -108,23 +121,28 @@ static bool make_plan(Plan& p, int64_t T, int d, int V, int n_seq, int n_groups,
   p.off_vstar = take((size_t)n_groups * 16);
   p.off_gw = take((size_t)((n_seq > 0 ? n_seq : 1) + n_groups) * 8);
   if (dtype == OAPL_BF16) {
-    p.off_Wp = take((size_t)p.n_rt_v * p.n_kt_d * kPackBlockBytes);
-    p.off_Hp = take((size_t)p.n_rt_T * p.n_kt_d * kPackBlockBytes);
+    p.off_Wp = take((size_t)p.n_rt_v * p.n_kt_d * kPackBlockBytesA);
+    {  // packed H: 384-row blocks, or 256-row blocks for the sampling kernel (whichever is larger)
+      const size_t a = (size_t)p.n_rt_T * p.n_kt_d * kPackBlockBytesB;
+      const size_t b = (size_t)((T + CfgSample::BN - 1) / CfgSample::BN > 0 ? (T + CfgSample::BN - 1) / CfgSample::BN : 1) *
+                       p.n_kt_d * CfgSample::STAGE_B;
+      p.off_Hp = take(a > b ? a : b);
+    }
   }
   if (bwd) {
     if (dtype == OAPL_BF16) {
-      p.off_WTp = take((size_t)p.n_rt_d * p.n_kt_v * kPackBlockBytes);
-      p.off_HTp = take((size_t)p.n_rt_d * p.n_kt_t * kPackBlockBytes);
-      p.off_G = take((size_t)(p.Tp / kPackRows) * p.n_kt_g * kPackBlockBytes);
-      p.off_GT = take((size_t)p.n_rt_v * p.n_kt_t * kPackBlockBytes);
+      p.off_WTp = take((size_t)p.n_rt_d * p.n_kt_v * kPackBlockBytesA);
+      p.off_HTp = take((size_t)p.n_rt_d * p.n_kt_t * kPackBlockBytesA);
+      p.off_G = take((size_t)(p.Tp / Cfg::BN) * p.n_kt_g * kPackBlockBytesB);
+      p.off_GT = take((size_t)p.n_rb_v * p.n_kt_t * kPackBlockBytesB);
       // single-sweep path: reference exponents, per-vocabulary-tile row sums of one panel, and a
       // second panel buffer pair (a panel's gradient contractions run after the next panel's sweep)
       p.sweep = true;
       p.off_ref2 = take(Tn * 4);
       p.off_spart = take((size_t)p.n_rt_v * (size_t)p.Tp * 4);
       if (T > p.Tp) {
-        p.off_G2 = take((size_t)(p.Tp / kPackRows) * p.n_kt_g * kPackBlockBytes);
-        p.off_GT2 = take((size_t)p.n_rt_v * p.n_kt_t * kPackBlockBytes);
+        p.off_G2 = take((size_t)(p.Tp / Cfg::BN) * p.n_kt_g * kPackBlockBytesB);
+        p.off_GT2 = take((size_t)p.n_rb_v * p.n_kt_t * kPackBlockBytesB);
       }
     } else {
       p.off_G = take((size_t)p.Tp * V * 4);
@@ -183,7 +201,7 @@ static bool prepare_kernels() {
   static bool ok = false;
   std::call_once(once, [] {
     ok = allow_big_lds(k_fwd_lse<Cfg, false>, Cfg::LDS_BYTES) && allow_big_lds(k_fwd_lse<Cfg, true>, Cfg::LDS_BYTES) &&
-         allow_big_lds(k_fwd_sample<Cfg>, Cfg::LDS_BYTES) && allow_big_lds(k_bwd_dz<Cfg>, Cfg::LDS_BYTES) &&
+         allow_big_lds(k_fwd_sample<CfgSample>, CfgSample::LDS_BYTES) && allow_big_lds(k_bwd_dz<Cfg>, Cfg::LDS_BYTES) &&
          allow_big_lds(k_bwd_dh<Cfg>, Cfg::LDS_BYTES) && allow_big_lds(k_bwd_dw<Cfg>, Cfg::LDS_BYTES) &&
          allow_big_lds(k_sweep<Cfg>, Cfg::LDS_BYTES);
   });
@@ -211,9 +229,10 @@ static int prepare_operands(const Plan& p, const void* H, const void* W, const i
     OAPL_LAUNCH_CHECK();
     bf16_t* Wp = (bf16_t*)(ws + p.off_Wp);
     bf16_t* Hp = (bf16_t*)(ws + p.off_Hp);
-    k_pack_rows<<<dim3(p.n_kt_d, p.n_rt_v), 256, 0, st>>>((const bf16_t*)W, p.V, p.d, p.d, Wp, p.n_kt_d);
+    k_pack_rows<<<dim3(p.n_kt_d, p.n_rt_v), 256, 0, st>>>((const bf16_t*)W, p.V, p.d, p.d, Wp, p.n_kt_d, Cfg::BM);
     OAPL_LAUNCH_CHECK();
-    k_pack_rows<<<dim3(p.n_kt_d, (unsigned)p.n_rt_T), 256, 0, st>>>((const bf16_t*)H, T, p.d, p.d, Hp, p.n_kt_d);
+    k_pack_rows<<<dim3(p.n_kt_d, (unsigned)p.n_rt_T), 256, 0, st>>>((const bf16_t*)H, T, p.d, p.d, Hp, p.n_kt_d,
+                                                                    Cfg::BN);
     OAPL_LAUNCH_CHECK();
   } else {
     k_gather_logit<float, double><<<grid1d(T, 4), 256, 0, st>>>((const float*)H, (const float*)W, tokens, T, p.d, p.V,
@@ -296,7 +315,8 @@ static int backward_grads(const Plan& p, const void* H, const void* W, const int
       OAPL_LAUNCH_CHECK();
     }
     const int MTv = p.n_rt_v, MTd = p.n_rt_d;
-    const int64_t strip_d = (int64_t)p.n_kt_d * (kPackBlockBytes / 2);
+    const int NTv = (V + Cfg::BN - 1) / Cfg::BN;   // vocabulary tiles on the n side (dW contraction)
+    const int64_t strip_d = (int64_t)p.n_kt_d * (kPackBlockBytesB / 2);   // one token tile of packed H
     for (int64_t t0 = 0; t0 < T; t0 += p.Tp) {
       const int64_t nv = (T - t0) < p.Tp ? (T - t0) : p.Tp;
       const int64_t Kt = round_up(nv, Cfg::BN);
@@ -308,7 +328,7 @@ static int backward_grads(const Plan& p, const void* H, const void* W, const int
       {
         ScopedKernelTimer tm(kBwdDz, st, timed);
         k_bwd_dz<Cfg><<<(unsigned)round_up(MTv * NTl, 8), Cfg::NT, Cfg::LDS_BYTES, st>>>(
-            Wp, Hp + (t0 / kPackRows) * strip_d, V, nv, p.n_kt_d, tokens + t0, lse2 + t0, inv + t0, G, p.n_kt_g, GT,
+            Wp, Hp + (t0 / Cfg::BN) * strip_d, V, nv, p.n_kt_d, tokens + t0, lse2 + t0, inv + t0, G, p.n_kt_g, GT,
             p.n_kt_t, gate);
       }
       OAPL_LAUNCH_CHECK();
@@ -320,7 +340,7 @@ static int backward_grads(const Plan& p, const void* H, const void* W, const int
       OAPL_LAUNCH_CHECK();
       {
         ScopedKernelTimer tm(kBwdDw, st, timed);
-        k_bwd_dw<Cfg><<<(unsigned)round_up((int64_t)MTd * MTv, 8), Cfg::NT, Cfg::LDS_BYTES, st>>>(
+        k_bwd_dw<Cfg><<<(unsigned)round_up((int64_t)MTd * NTv, 8), Cfg::NT, Cfg::LDS_BYTES, st>>>(
             HTp, GT, p.n_kt_t, d, V, (int)(Kt / kPackK), dW, t0 > 0 ? 1 : 0, gate);
       }
       OAPL_LAUNCH_CHECK();
@@ -384,7 +404,8 @@ static int sweep_path(const Plan& p, const void* H, const void* W, const int32_t
   float* nis = (float*)(ws + p.off_inv);
   const float* coef = (const float*)(ws + p.off_coef);
   const int MTv = p.n_rt_v, MTd = p.n_rt_d;
-  const int64_t strip_d = (int64_t)p.n_kt_d * (kPackBlockBytes / 2);
+  const int NTv = (V + Cfg::BN - 1) / Cfg::BN;     // vocabulary tiles on the n side (dW contraction)
+  const int64_t strip_d = (int64_t)p.n_kt_d * (kPackBlockBytesB / 2);   // one token tile of packed H
   const int64_t n_tiles = (T + Cfg::BN - 1) / Cfg::BN;
 
   k_sweep_plan<<<grid1d(p.n_seq > 0 ? p.n_seq : 1, 256), 256, 0, st>>>(seq_offsets, p.n_seq, T, p.Tp, flag);
@@ -422,7 +443,7 @@ static int sweep_path(const Plan& p, const void* H, const void* W, const int32_t
     OAPL_LAUNCH_CHECK();
     {
       ScopedKernelTimer tm(kBwdDw, st);
-      k_bwd_dw<Cfg><<<(unsigned)round_up((int64_t)MTd * MTv, 8), Cfg::NT, Cfg::LDS_BYTES, st>>>(
+      k_bwd_dw<Cfg><<<(unsigned)round_up((int64_t)MTd * NTv, 8), Cfg::NT, Cfg::LDS_BYTES, st>>>(
           HTp, GTbuf[k & 1], p.n_kt_t, d, V, (int)(Kt / kPackK), dW, k > 0 ? 1 : 0, fast);
     }
     OAPL_LAUNCH_CHECK();
@@ -435,7 +456,7 @@ static int sweep_path(const Plan& p, const void* H, const void* W, const int32_t
     {
       ScopedKernelTimer tm(kSweep, st);
       k_sweep<Cfg><<<(unsigned)round_up(MTv * NTl, 8), Cfg::NT, Cfg::LDS_BYTES, st>>>(
-          Wp, Hp + (t0 / kPackRows) * strip_d, V, nv, p.n_kt_d, ref2 + t0, Gbuf[k & 1], p.n_kt_g, GTbuf[k & 1],
+          Wp, Hp + (t0 / Cfg::BN) * strip_d, V, nv, p.n_kt_d, ref2 + t0, Gbuf[k & 1], p.n_kt_g, GTbuf[k & 1],
           p.n_kt_t, spart, p.Tp, fast);
     }
     OAPL_LAUNCH_CHECK();
@@ -644,15 +665,17 @@ int32_t oapl_sample_tokens(const void* H, const void* W, int64_t T, int32_t d, i
     if (!prepare_kernels()) return OAPL_ERR_HIP;
     bf16_t* Wp = (bf16_t*)(ws + p.off_Wp);
     bf16_t* Hp = (bf16_t*)(ws + p.off_Hp);
-    k_pack_rows<<<dim3(p.n_kt_d, p.n_rt_v), 256, 0, st>>>((const bf16_t*)W, V, d, d, Wp, p.n_kt_d);
+    k_pack_rows<<<dim3(p.n_kt_d, p.n_rt_v), 256, 0, st>>>((const bf16_t*)W, V, d, d, Wp, p.n_kt_d, Cfg::BM);
     OAPL_LAUNCH_CHECK();
-    k_pack_rows<<<dim3(p.n_kt_d, (unsigned)p.n_rt_T), 256, 0, st>>>((const bf16_t*)H, T, d, d, Hp, p.n_kt_d);
+    const int64_t n_tiles = (T + CfgSample::BN - 1) / CfgSample::BN;
+    k_pack_rows<<<dim3(p.n_kt_d, (unsigned)n_tiles), 256, 0, st>>>((const bf16_t*)H, T, d, d, Hp, p.n_kt_d,
+                                                                   CfgSample::BN);
     OAPL_LAUNCH_CHECK();
-    const int64_t total = p.n_rt_T * p.n_parts;
+    const int64_t total = n_tiles * p.n_parts_s;
     {
       ScopedKernelTimer tm(kFwdSample, st);
-      k_fwd_sample<Cfg><<<(unsigned)round_up(total, 8), Cfg::NT, Cfg::LDS_BYTES, st>>>(
-          Wp, Hp, V, T, p.n_kt_d, p.n_parts, inv_t, s_lo, s_hi, partials);
+      k_fwd_sample<CfgSample><<<(unsigned)round_up(total, 8), CfgSample::NT, CfgSample::LDS_BYTES, st>>>(
+          Wp, Hp, V, T, p.n_kt_d, p.n_parts_s, inv_t, s_lo, s_hi, partials);
     }
     OAPL_LAUNCH_CHECK();
   } else {
@@ -661,7 +684,7 @@ int32_t oapl_sample_tokens(const void* H, const void* W, int64_t T, int32_t d, i
     k_gemm_f32<<<grid, 256, 0, st>>>(A, B, T, (int64_t)V, (int64_t)d, EpiSampleF32{partials, T, inv_t, s_lo, s_hi});
     OAPL_LAUNCH_CHECK();
   }
-  k_sample_finish<<<grid1d(T, 256), 256, 0, st>>>(partials, p.n_parts, T, tokens_out, score_out);
+  k_sample_finish<<<grid1d(T, 256), 256, 0, st>>>(partials, p.n_parts_s, T, tokens_out, score_out);
   OAPL_LAUNCH_CHECK();
   return OAPL_OK;
 }

@@ -385,9 +385,12 @@ k_sweep_finish(const float* __restrict__ spart, int n_vt, int64_t ld_s, int64_t 
   const int y = tokens[n];
   if (y >= 0 && y < V) {
     const bf16_t patch = (bf16_t)(float)(S * expm1(lp));       // -S (1 - p_y)
-    const int64_t blk = kPackRows * kPackK;                    // elements of a packed block
-    Gp[((n >> 8) * g_n_kt + (y >> 6)) * blk + (n & 255) * kPackK + (y & 63)] = patch;
-    GTp[(((int64_t)(y >> 8)) * gt_n_kt + (n >> 6)) * blk + (y & 255) * kPackK + (n & 63)] = patch;
+    // both copies are n-side operands: blocks of kPackRowsB rows x 64 k
+    const int64_t blk = (int64_t)kPackRowsB * kPackK;             // elements of a packed block
+    const int64_t nb = n / kPackRowsB, nr = n - nb * kPackRowsB;  // token row block / row inside it
+    const int yb = y / kPackRowsB, yr = y - yb * kPackRowsB;      // vocabulary row block / row inside it
+    Gp[(nb * g_n_kt + (y >> 6)) * blk + nr * kPackK + (y & 63)] = patch;
+    GTp[((int64_t)yb * gt_n_kt + (n >> 6)) * blk + (int64_t)yr * kPackK + (n & 63)] = patch;
   }
 }
 

@@ -26,7 +26,7 @@ from tests._util import f64, grad_norm, rel
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
-PANEL_ROWS = 65536      # the library's largest backward panel; rows around its multiples are sampled
+PANEL_ROWS = (49152, 61440)     # panel sizes the library picks at these T; rows around their multiples are sampled
 
 
 def _sample_rows(off, T, n_random, seed):
@@ -35,13 +35,14 @@ def _sample_rows(off, T, n_random, seed):
         if off[s + 1] > off[s]:
             rows.add(int(off[s]))
             rows.add(int(off[s + 1] - 1))
-    for edge in (0, 255, 256, 257, 511, 512, T - 257, T - 256, T - 1):
+    for edge in (0, 191, 192, 255, 256, 383, 384, 385, 767, 768, T - 385, T - 384, T - 1):   # token-tile edges
         if 0 <= edge < T:
             rows.add(int(edge))
-    for k in range(1, T // PANEL_ROWS + 1):
-        for e in (k * PANEL_ROWS - 1, k * PANEL_ROWS, k * PANEL_ROWS + 1):
-            if 0 <= e < T:
-                rows.add(int(e))
+    for panel in PANEL_ROWS:
+        for k in range(1, T // panel + 1):
+            for e in (k * panel - 1, k * panel, k * panel + 1):
+                if 0 <= e < T:
+                    rows.add(int(e))
     rng = np.random.default_rng(seed)
     rows.update(int(x) for x in rng.integers(0, T, size=n_random))
     return np.array(sorted(rows), dtype=np.int64)
