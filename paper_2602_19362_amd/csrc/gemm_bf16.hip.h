@@ -387,6 +387,9 @@ __device__ __forceinline__ void stage_mn_pk(lds_char_ptr smem, const uint32_t (&
 // Tile coordinates for a logical workgroup id: tiles are walked in strips of
 // SN tiles along n, m fastest within a strip row, so that the ~32 workgroups
 // resident on one XCD form a (32 / SN) x SN patch and share operand panels.
+// The kernels use SN = 4: an 8 x 4 patch of 256 x 384 tiles needs 8 x 32 KB +
+// 4 x 48 KB of operands per k-step, the least for 32 tiles (measured +1.5 %
+// over 4 x 8, and 8 % over 2 x 16).
 template <int SN>
 __device__ __forceinline__ void strip_tile(int L, int MT, int NTl, int& mt, int& nt) {
   const int per_strip = SN * MT;
@@ -666,7 +669,7 @@ k_bwd_dz(const bf16_t* __restrict__ Wp, const bf16_t* __restrict__ Hp_panel, int
   const int L = xcd_logical_id(blockIdx.x, total);
   if (L >= total) return;
   int mt, nt;
-  strip_tile<8>(L, MT, NTl, mt, nt);
+  strip_tile<4>(L, MT, NTl, mt, nt);
   const int m0 = mt * C::BM;
   const int64_t n0 = (int64_t)nt * C::BN;
   const int64_t strip_a = (int64_t)n_kt * (C::STAGE_A / 2), strip_b = (int64_t)n_kt * (C::STAGE_B / 2);
@@ -769,7 +772,7 @@ k_sweep(const bf16_t* __restrict__ Wp, const bf16_t* __restrict__ Hp_panel, int 
   const int L = xcd_logical_id(blockIdx.x, total);
   if (L >= total) return;
   int mt, nt;
-  strip_tile<8>(L, MT, NTl, mt, nt);
+  strip_tile<4>(L, MT, NTl, mt, nt);
   const int m0 = mt * C::BM;
   const int64_t n0 = (int64_t)nt * C::BN;
   const int64_t strip_a = (int64_t)n_kt * (C::STAGE_A / 2), strip_b = (int64_t)n_kt * (C::STAGE_B / 2);
@@ -878,7 +881,7 @@ k_bwd_dh(const bf16_t* __restrict__ WTp, int wt_n_kt, const bf16_t* __restrict__
   const int L = xcd_logical_id(blockIdx.x, total);
   if (L >= total) return;
   int mt, nt;
-  strip_tile<8>(L, MT, NTl, mt, nt);
+  strip_tile<4>(L, MT, NTl, mt, nt);
   const int m0 = mt * C::BM;
   const int64_t n0 = (int64_t)nt * C::BN;
 
@@ -931,7 +934,7 @@ k_bwd_dw(const bf16_t* __restrict__ HTp, const bf16_t* __restrict__ GTp, int t_n
   const int L = xcd_logical_id(blockIdx.x, total);
   if (L >= total) return;
   int mt, nt;
-  strip_tile<8>(L, MT, NTl, mt, nt);
+  strip_tile<4>(L, MT, NTl, mt, nt);
   const int m0 = mt * C::BM;
   const int n0 = nt * C::BN;
 
