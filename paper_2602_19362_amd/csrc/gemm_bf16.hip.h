@@ -80,6 +80,15 @@ typedef __attribute__((address_space(3))) char* lds_char_ptr;
 // vmcnt in bits [3:0] and [15:14]; expcnt and lgkmcnt fields left at their maximum = no wait).
 __host__ __device__ constexpr int vmcnt_imm(int n) { return (n & 15) | ((n >> 4) << 14) | 0x0F70; }
 
+// Workgroup barrier for LDS hand-offs in epilogues: waits for this wave's LDS operations only.
+// __syncthreads() also waits for the wave's outstanding global stores (vmcnt(0)), i.e. for a round
+// trip to memory at every hand-off; the data of a store that has been issued is already out of the
+// registers, so nothing here needs that wait.
+__device__ __forceinline__ void lds_barrier() {
+  __builtin_amdgcn_s_waitcnt(0xC07F);   // lgkmcnt(0); vmcnt and expcnt fields at their maximum = no wait
+  __builtin_amdgcn_s_barrier();
+}
+
 template <class C>
 struct Mainloop {
   // 16-byte chunk c of LDS row `row` lives at physical chunk c ^ ((row >> 1) & 7).  The operand
@@ -333,12 +342,15 @@ __device__ __forceinline__ void store_tile_both_ways(lds_char_ptr smem, const f3
 // Half the registers of the fp32 tile, so nothing spills around the stores.
 // ---------------------------------------------------------------------------
 
-// Copy with rows = n, k = m, straight from registers: a lane owns 4 consecutive m (8 bytes) of its
-// row n per (i, q), the two lane halves own adjacent 8 bytes, and a wave row covers whole 128-byte
-// rows of a k-block, which the L2 merges into full lines.  `strip` is block (n-tile, 0) of the
-// destination, kb0 the first k-block (m0 / 64).
+// Copy with rows = n, k = m, straight from registers.  A lane owns 4 consecutive m (8 bytes) of its
+// row n per (i, q) and the other lane half owns the 8 bytes next to them, so the 64 bytes of row n
+// that one MFMA block covers are spread over two lanes in 8-byte pieces.  The halves first trade
+// registers (v_permlane32_swap: the lower half hands over its pieces q = 2, 3 and receives the
+// upper half's q = 0, 1), after which each lane holds 32 contiguous bytes and stores them as two
+// 16-byte words: half as many store instructions, twice the bytes per address.  Destroys pk.
+// `strip` is block (n-tile, 0) of the destination, kb0 the first k-block (m0 / 64).
 template <class C>
-__device__ __forceinline__ void store_nm_packed_direct(const uint32_t (&pk)[C::TM][C::TN][8], bf16_t* strip, int kb0) {
+__device__ __forceinline__ void store_nm_packed_direct(uint32_t (&pk)[C::TM][C::TN][8], bf16_t* strip, int kb0) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int wm = wave / C::WN, wn = wave % C::WN;
   const int h = lane >> 5;
@@ -349,38 +361,59 @@ __device__ __forceinline__ void store_nm_packed_direct(const uint32_t (&pk)[C::T
     for (int i = 0; i < C::TM; ++i) {
       const int m_blk = wm * C::TM * 32 + i * 32;              // multiple of 32: k-block m_blk / 64, half m_blk % 64
       char* dst = (char*)strip + (int64_t)(kb0 + m_blk / kPackK) * C::STAGE_B + n_l * kPackRowBytes +
-                  ((m_blk % kPackK) + 4 * h) * 2;
+                  (m_blk % kPackK) * 2 + 32 * h;
+      uint32_t a[4], b[4];
 #pragma unroll
-      for (int q = 0; q < 4; ++q) *(u32x2*)(dst + 16 * q) = u32x2{pk[i][j][2 * q], pk[i][j][2 * q + 1]};
+      for (int e = 0; e < 4; ++e) {
+        // a: own word (lower lanes) / the lower half's word e + 4 (upper lanes);  b: the upper half's word e / own
+        const auto r = __builtin_amdgcn_permlane32_swap(pk[i][j][e], pk[i][j][e + 4], false, false);
+        a[e] = r[0];
+        b[e] = r[1];
+      }
+      *(u32x4*)(dst) = u32x4{a[0], a[1], b[0], b[1]};
+      *(u32x4*)(dst + 16) = u32x4{a[2], a[3], b[2], b[3]};
     }
   }
 }
 
-// LDS chunk [m][n] from the packed pairs.  Neighbouring lanes (columns n, n + 1) swap halves so
-// that each lane writes 4 bytes: the even lane row m (its own low half, the neighbour's low half),
-// the odd lane row m + 1 (the neighbour's high half, its own high half).
+// LDS chunk [m][n] from the packed pairs: chunk i holds MFMA block row i of every wave row (32 rows
+// each, WM * 32 rows in all), so all waves stage at once.  Neighbouring lanes (columns n, n + 1) swap
+// halves so that each lane writes 4 bytes: the even lane row m (its own low half, the neighbour's
+// low half), the odd lane row m + 1 (the neighbour's high half, its own high half).
 template <class C>
-__device__ __forceinline__ void stage_mn_pk(lds_char_ptr smem, const uint32_t (&pk)[C::TM][C::TN][8], int chunk) {
-  constexpr int WPC = C::WM / C::MN_CHUNKS;   // wave rows per chunk
+__device__ __forceinline__ void stage_mn_pk(lds_char_ptr smem, const uint32_t (&pk)[C::TM][C::TN][8], const int i) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int wm = wave / C::WN, wn = wave % C::WN;
   const int h = lane >> 5, odd = lane & 1;
-  if (wm / WPC != chunk) return;
   // v_perm_b32 picks bytes from {neighbour (4..7), own (0..3)}
   const uint32_t sel = odd ? 0x03020706u : 0x05040100u;
 #pragma unroll
   for (int j = 0; j < C::TN; ++j) {
     const int n_l = wn * C::TN * 32 + j * 32 + (lane & 31) - odd;
 #pragma unroll
-    for (int i = 0; i < C::TM; ++i)
-#pragma unroll
-      for (int p = 0; p < 8; ++p) {
-        const uint32_t own = pk[i][j][p];
-        const uint32_t nbr = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)own, 0xB1 /* quad_perm 1,0,3,2 */, 0xF, 0xF, true);
-        const uint32_t w = __builtin_amdgcn_perm(nbr, own, sel);
-        const int m_l = (wm % WPC) * C::TM * 32 + acc_row(i, 2 * p) + 4 * h + odd;
-        *(__attribute__((address_space(3))) uint32_t*)(smem + m_l * C::PITCH_MN + n_l * 2) = w;
-      }
+    for (int p = 0; p < 8; ++p) {
+      const uint32_t own = pk[i][j][p];
+      const uint32_t nbr = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)own, 0xB1 /* quad_perm 1,0,3,2 */, 0xF, 0xF, true);
+      const uint32_t w = __builtin_amdgcn_perm(nbr, own, sel);
+      const int m_l = wm * 32 + acc_row(0, 2 * p) + 4 * h + odd;
+      *(__attribute__((address_space(3))) uint32_t*)(smem + m_l * C::PITCH_MN + n_l * 2) = w;
+    }
+  }
+}
+
+// Chunk i staged by stage_mn_pk -> packed n-side matrix whose rows are the m index (global row
+// m0 + ..., blocks of BN rows) and whose k index is n; n_kt is the destination's strip pitch in
+// k-blocks, kb0 the first k-block (n0 / 64).
+template <class C>
+__device__ __forceinline__ void store_mn_pk_packed(lds_char_ptr smem, bf16_t* base, int n_kt, int m0, int kb0, int i) {
+  constexpr int CH = C::BN / 8;
+  for (int idx = threadIdx.x; idx < C::WM * 32 * CH; idx += C::NT) {
+    const int m_l = idx / CH, ch = idx % CH;
+    const int m = m0 + (m_l >> 5) * (C::TM * 32) + i * 32 + (m_l & 31);
+    const int blk = m / C::BN, r = m - blk * C::BN;
+    const u32x4 v = *(const __attribute__((address_space(3))) u32x4*)(smem + m_l * C::PITCH_MN + ch * 16);
+    char* dst = (char*)base + ((int64_t)blk * n_kt + kb0 + (ch >> 3)) * C::STAGE_B;
+    *(u32x4*)(dst + r * kPackRowBytes + (ch & 7) * 16) = v;
   }
 }
 
@@ -833,15 +866,13 @@ k_sweep(const bf16_t* __restrict__ Wp, const bf16_t* __restrict__ Hp_panel, int 
       }
     csum[j] = sum + __shfl_xor(sum, 32, 64);     // the two lane halves hold the same token
   }
-  // Gp: rows = tokens (n), k = vocabulary (m), straight from the registers
-  store_nm_packed_direct<C>(pk, Gp + (int64_t)nt * g_n_kt * (C::STAGE_B / 2), m0 / kPackK);
   // row sums: the WM waves stacked along the vocabulary, through LDS, in a fixed order
   __attribute__((address_space(3))) float* red = (__attribute__((address_space(3))) float*)smem;
   if (h == 0) {
 #pragma unroll
     for (int j = 0; j < C::TN; ++j) red[wm * C::BN + wn * C::TN * 32 + j * 32 + lane] = csum[j];
   }
-  __syncthreads();
+  lds_barrier();
   for (int n_l = threadIdx.x; n_l < C::BN; n_l += C::NT) {
     if (n0 + n_l < n_valid) {
       float a = red[n_l];
@@ -850,15 +881,19 @@ k_sweep(const bf16_t* __restrict__ Wp, const bf16_t* __restrict__ Hp_panel, int 
       spart[(int64_t)mt * ld_s + n0 + n_l] = a;
     }
   }
-  __syncthreads();
-  // GTp: rows = vocabulary (m), k = tokens (n), through LDS in chunks of wave rows
-#pragma unroll 1
-  for (int c = 0; c < C::MN_CHUNKS; ++c) {
-    stage_mn_pk<C>(smem, pk, c);
-    __syncthreads();
-    store_mn_packed<C>(smem, GTp, gt_n_kt, m0, (int)(n0 / kPackK), c);
-    __syncthreads();
+  lds_barrier();
+  // GTp: rows = vocabulary (m), k = tokens (n), through LDS, one MFMA block row of every wave at a time
+  static_assert(C::WM * 32 * C::PITCH_MN <= C::LDS_BYTES, "staging chunk must fit");
+#pragma unroll
+  for (int i = 0; i < C::TM; ++i) {
+    if (i > 0) lds_barrier();
+    stage_mn_pk<C>(smem, pk, i);
+    lds_barrier();
+    store_mn_pk_packed<C>(smem, GTp, gt_n_kt, m0, (int)(n0 / kPackK), i);
   }
+  // Gp: rows = tokens (n), k = vocabulary (m), straight from the registers (last: it consumes pk,
+  // and its stores drain after the workgroup has gone)
+  store_nm_packed_direct<C>(pk, Gp + (int64_t)nt * g_n_kt * (C::STAGE_B / 2), m0 / kPackK);
 }
 
 // ---------------------------------------------------------------------------
