@@ -149,7 +149,7 @@ int32_t oapl_sample_tokens(const void* H, const void* W, int64_t T, int32_t d, i
  *               dW[v,:] = sum_t c_t (1[v = y_t] - p_{t,v}) H[t,:]
  *
  * How the gradients are scheduled (bf16): the logits are visited ONCE.  Panels of
- * at most 65536 token rows are swept with the soft-max written unnormalised
+ * at most 61440 token rows are swept with the soft-max written unnormalised
  * (bf16, against a per-row reference exponent fixed before the sweep), their
  * row sums give lse and the log-probs, and the dH / dW contractions consume a
  * panel as soon as every rollout touching it is scored.  That needs (a) no
