@@ -159,6 +159,9 @@ struct Mainloop {
 #pragma unroll
       for (int j = 0; j < C::TN; ++j)
         b[j] = *(const __attribute__((address_space(3))) bf16x8*)(smem + STAGE * C::STAGE_B + rdB[ks] + j * 32 * C::ROW_BYTES);
+      // all reads of a k-step are issued before its first multiplication; the scheduler then overlaps
+      // them with the previous k-step's last multiplications instead of starting every k-step by waiting
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int i = 0; i < C::TM; ++i)
 #pragma unroll
