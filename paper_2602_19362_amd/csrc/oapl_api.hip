@@ -25,7 +25,6 @@ static_assert(Cfg::BN == kPackRowsB, "n-side operands of the loss path are packe
 typedef TileCfg<4, 2, 2, 4, 2> CfgSample;
 
 constexpr int64_t kPanelBf16 = 61440;  // most token rows per backward panel (bf16 path): 160 token tiles
-constexpr int64_t kPanelUnit = 6144;   // 16 token tiles: whole rounds of workgroups in the dH contraction at d = 4096
 constexpr int64_t kPanelF32 = 4096;    // ... (fp32 path)
 constexpr int kStatusWords = 64;       // 256-byte header
 constexpr int kNumCU = 256;            // MI355X compute units (one 128 KB-LDS workgroup each)
@@ -85,13 +84,26 @@ static bool make_plan(Plan& p, int64_t T, int d, int V, int n_seq, int n_groups,
     };
     p.n_parts = pick_splits(n_tiles);
     p.n_parts_s = pick_splits((T + CfgSample::BN - 1) / CfgSample::BN);
-    // equal panels of at most kPanelBf16 rows (a short last panel would waste a whole pass
-    // of the fp32 read-add-write over dW)
-    const int64_t n_panels = T > 0 ? (T + kPanelBf16 - 1) / kPanelBf16 : 1;
-    // with several panels, a panel of a multiple of 6144 rows gives the dH contraction (d / 256 x
-    // Tp / 384 tiles) whole rounds of kNumCU workgroups when d is a multiple of 4096
-    p.Tp = round_up(T > 0 ? (T + n_panels - 1) / n_panels : 1, n_panels > 1 ? kPanelUnit : Cfg::BN);
-    if (p.Tp > kPanelBf16) p.Tp = kPanelBf16;
+    // Panel size: a multiple of the token tile, at most kPanelBf16 rows.  One panel if T fits; otherwise
+    // the size (between half the cap and the cap) that costs the fewest rounds of kNumCU workgroups in
+    // the dH contraction -- its tiles (d / 256 x panel rows / 384, each K = V long) are few and long, so
+    // a partly filled last round is expensive -- plus a charge per panel for the fp32 read-add-write
+    // pass over dW.  Ties go to the larger panel (longer rollouts fit the single sweep).
+    if (T <= kPanelBf16) {
+      p.Tp = round_up(T > 0 ? T : 1, Cfg::BN);
+    } else {
+      const int64_t mtd = (d + Cfg::BM - 1) / Cfg::BM;
+      const int64_t k_max = kPanelBf16 / Cfg::BN;
+      double best = 1e300;
+      for (int64_t k = k_max; k >= k_max / 2; --k) {
+        const int64_t rows = k * Cfg::BN;
+        const int64_t full = T / rows, rest = T - full * rows;
+        const int64_t rounds_full = (mtd * k + kNumCU - 1) / kNumCU;
+        const int64_t rounds_rest = (mtd * ((rest + Cfg::BN - 1) / Cfg::BN) + kNumCU - 1) / kNumCU;
+        const double cost = (double)(full * rounds_full + rounds_rest) + 0.35 * (double)(full + (rest > 0 ? 1 : 0));
+        if (cost < best - 1e-9) { best = cost; p.Tp = rows; }
+      }
+    }
     p.n_rt_v = MT;
     p.n_rb_v = (int)(round_up((int64_t)MT * Cfg::BM, Cfg::BN) / Cfg::BN);
     p.n_rt_d = (d + Cfg::BM - 1) / Cfg::BM;

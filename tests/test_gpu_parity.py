@@ -125,8 +125,8 @@ def test_bf16_ragged_shapes(d, V, lens, seed):
 
 
 def test_bf16_several_backward_panels():
-    """T = 150 001 spans three backward panels (55 296 rows each, the last one ragged); rollouts 1 and
-    4 straddle the panel boundaries at 55 296 and 110 592."""
+    """T = 150 001 spans three backward panels (61 440 rows, the last one ragged); rollouts 2 and 4
+    straddle the panel boundaries at 61 440 and 122 880."""
     lens = [50000, 9000, 40000, 233, 50768, 0]
     b = _custom_batch("bf16", d=64, V=520, lens=lens, n_groups=2, seed=5, beta=1.0, noise=0.02)
     res = _run(b)
@@ -135,7 +135,7 @@ def test_bf16_several_backward_panels():
 
 
 def test_bf16_rollout_longer_than_a_panel_takes_two_passes():
-    """A 65 536-token rollout does not fit one 55 296-row panel: the device sends the call down the
+    """A 65 536-token rollout does not fit one 61 440-row panel: the device sends the call down the
     two-pass schedule, with the same results."""
     lens = [65536, 9000, 40000, 233, 35232, 0]
     b = _custom_batch("bf16", d=64, V=520, lens=lens, n_groups=2, seed=5, beta=1.0, noise=0.02)
