@@ -49,6 +49,10 @@ struct Plan {
 };
 
 constexpr int kFlagWord = 8;   // status word that selects the two-pass path on the device
+// The single sweep rounds the sampled token's gradient entry to bf16 (2^-9 relative, a common factor of
+// that token's whole gradient row); over a batch these roundings average out, for a handful of tokens
+// they show in the gradient norm.  Smaller batches take the two-pass path, whose one-hot entry is exact.
+constexpr int64_t kSweepMinTokens = 64;
 
 // Process-wide switch for the single-sweep loss path (on by default).
 static bool g_single_sweep = true;
@@ -539,7 +543,7 @@ static int loss_impl(const void* H, const void* W, const int32_t* tokens, const 
   if (int rc = prepare_operands(p, H, W, tokens, ws, st)) return rc;
   // bf16 with gradients: one sweep over the logits; the two-pass path behind it runs only if the
   // sweep's preconditions fail on this call's data (decided on the device, in stream order)
-  const bool sweep = bwd && T > 0 && p.sweep && g_single_sweep;
+  const bool sweep = bwd && T >= kSweepMinTokens && p.sweep && g_single_sweep;
   Gate slow = kNoGate;
   if (sweep) {
     if (int rc = sweep_path(p, H, W, tokens, logq, seq_offsets, logprob_out, dH, dW, ws, st, objective)) return rc;
@@ -599,7 +603,7 @@ static int grpo_impl(const void* H, const void* W, const int32_t* tokens, const 
                                       (double)loss_scale, gstat, gstat + n_groups, adv, wseq, adv_out, status,
                                       kNoGate);
   OAPL_LAUNCH_CHECK();
-  const bool sweep = bwd && T > 0 && p.sweep && g_single_sweep;
+  const bool sweep = bwd && T >= kSweepMinTokens && p.sweep && g_single_sweep;
   Gate slow = kNoGate;
   if (sweep) {
     if (int rc = sweep_path(p, H, W, tokens, logq, seq_offsets, logprob_out, dH, dW, ws, st, objective)) return rc;

@@ -36,8 +36,8 @@ def schedule(request):
 
 
 def _sweep_tried(b, res):
-    """True if the call tries the single sweep first (switched on, bf16, with gradients, not empty)."""
-    return _MODE[0] == "single_sweep" and b.H.dtype == torch.bfloat16 and res.dH is not None and b.T > 0
+    """True if the call tries the single sweep first (switched on, bf16, with gradients, at least 64 tokens)."""
+    return _MODE[0] == "single_sweep" and b.H.dtype == torch.bfloat16 and res.dH is not None and b.T >= 64
 
 
 def _run(b, **kw):
@@ -122,6 +122,20 @@ def test_bf16_ragged_shapes(d, V, lens, seed):
     res = _run(b)
     ref = oracle_full(b)
     _check(b, res, ref, lp_tol=2e-2, rel_tol=1e-3, g_rtol=2e-2, g_atol_frac=6e-3)
+
+
+@pytest.mark.parametrize("d,V,lens", [(8, 8, [1]), (16, 3, [2, 1]), (8, 300, [1, 0, 1]), (64, 2, [5])])
+def test_bf16_smallest_shapes(d, V, lens):
+    """One token, a vocabulary of two or three, a hidden size of one 16-byte row: far below one tile in
+    every dimension (all padding paths at once)."""
+    b = _custom_batch("bf16", d=d, V=V, lens=lens, n_groups=1, seed=17, beta=1.0, noise=0.3)
+    res = _run(b)
+    ref = oracle_full(b)
+    _check(b, res, ref, lp_tol=2e-2, rel_tol=1e-3, g_rtol=2e-2, g_atol_frac=6e-3)
+    lp, ent, _ = oapl.logprob_fwd(b.H, b.W, b.tokens, want_entropy=True)
+    assert np.abs(f64(lp) - ref["logprob"]).max() <= 2e-2
+    tok, _ = oapl.sample_tokens(b.H, b.W, 1.0, 5)
+    assert int(tok.min()) >= 0 and int(tok.max()) < V
 
 
 def test_bf16_several_backward_panels():
