@@ -30,11 +30,11 @@ PEAK_BF16_TFLOPS = 2516.6     # MI355X dense bf16 MFMA: 256 CU x 4096 flop/clk x
 # sources at run time and the figure is reported as null when they differ.
 TRAFFIC = {
     "workload": "qwen7b",
-    "sources_sha256_16": "1f79d07dd527f39f",
-    "per_launch_bytes": {
-        "k_sweep": {"read": 68.59e9, "write": 28.69e9},
-        "k_bwd_dh": {"read": 72.25e9, "write": 0.38e9},
-        "k_bwd_dw": {"read": 79.48e9, "write": 2.50e9},
+    "sources_sha256_16": "05c4fd4f4b82386c",
+    "per_launch_bytes": {          # averages over the step's three panels (61440, 61440, 18017 rows)
+        "k_sweep": {"read": 70.76e9, "write": 28.69e9},
+        "k_bwd_dh": {"read": 68.55e9, "write": 0.38e9},
+        "k_bwd_dw": {"read": 79.50e9, "write": 2.49e9},
     },
 }
 

@@ -27,7 +27,7 @@ typedef TileCfg<4, 2, 2, 4, 2> CfgSample;
 constexpr int64_t kPanelBf16 = 61440;  // most token rows per backward panel (bf16 path): 160 token tiles
 constexpr int64_t kPanelF32 = 4096;    // ... (fp32 path)
 constexpr int kStatusWords = 64;       // 256-byte header
-constexpr int kNumCU = 256;            // MI355X compute units (one 128 KB-LDS workgroup each)
+constexpr int kNumCU = 256;            // MI355X compute units (one workgroup of the dense kernels each: it fills the LDS)
 
 static inline int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
 
@@ -61,7 +61,7 @@ static bool make_plan(Plan& p, int64_t T, int d, int V, int n_seq, int n_groups,
   if (T < 0 || d < 1 || V < 1 || n_seq < 0 || n_groups < 1) return false;
   if (dtype != OAPL_F32 && dtype != OAPL_BF16) return false;
   if (dtype == OAPL_BF16 && (d % 8) != 0) return false;
-  // a packed row-tile strip (K / 64 blocks of 32 KiB) must stay below 2 GiB for 32-bit buffer offsets,
+  // a packed row-tile strip (K / 64 blocks of 32 or 48 KiB) must stay below 2 GiB for 32-bit buffer offsets,
   // and the packing kernels index token tiles with gridDim.y
   if ((int64_t)d > (1 << 21) || (int64_t)V > (1 << 21)) return false;
   if (dtype == OAPL_BF16 && T > (int64_t)65535 * 256) return false;
