@@ -107,3 +107,12 @@ def test_product_path_has_no_cpu_fallback():
     tok = torch.zeros(4, dtype=torch.int32)
     with pytest.raises(ValueError):
         oapl.logprob_fwd(H, W, tok)       # host tensors are refused, nothing is computed on the CPU
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode != 0 and "one GPU" in r.stderr + r.stdout

@@ -268,6 +268,21 @@ def _check_samples(H, W, temperature, seed, tok_gpu, score_gpu, rows=None, tol=2
     return diff.size
 
 
+def test_per_rollout_entropy_from_the_segmented_sum():
+    """Per-rollout mean entropy (the curve of Sec. 6.1): per-token entropies through oapl_segmented_sum_f32."""
+    from oracle import oapl_oracle as orc
+    b = _custom_batch("bf16", d=128, V=900, lens=[120, 0, 33, 1, 250], n_groups=1, seed=33, beta=1.0)
+    _, ent, _ = oapl.logprob_fwd(b.H, b.W, b.tokens, want_entropy=True)
+    sums = oapl.segmented_sum_f32(ent, b.seq_offsets)
+    torch.cuda.synchronize()
+    off = b.seq_offsets.cpu().numpy()
+    ref = orc.token_entropy(f64(b.H), f64(b.W))
+    want = np.array([ref[off[s]:off[s + 1]].sum() for s in range(len(off) - 1)])
+    lens = np.diff(off)
+    assert np.all(np.abs(f64(sums) - want) <= 2e-2 * np.maximum(lens, 1))
+    assert f64(sums)[1] == 0.0          # an empty rollout sums to exactly zero
+
+
 @pytest.mark.parametrize("dtype,d,V,T,temp", [("f32", 40, 777, 300, 1.0), ("bf16", 128, 3000, 700, 1.0),
                                               ("bf16", 320, 1000, 515, 0.6), ("bf16", 64, 264, 100, 2.0)])
 def test_gumbel_max_sampling_matches_the_oracle_draws(dtype, d, V, T, temp):
