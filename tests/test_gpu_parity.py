@@ -572,3 +572,23 @@ def test_loss_call_replays_from_a_hip_graph():
         assert oapl.read_device_status(ws) == 0
         for got, ref in zip((captured.loss, captured.logprob, captured.seq_logratio, dH, dW), want):
             assert torch.equal(got, ref), k
+
+
+def test_calls_on_two_streams_with_own_workspaces_do_not_interfere():
+    """Two batches enqueued on two streams (default priority), each with its own workspace and outputs:
+    the results are bit for bit those of the same calls made one after the other."""
+    ba = _custom_batch("bf16", d=128, V=1100, lens=[300, 41, 260], n_groups=1, seed=50, beta=0.8)
+    bb = _custom_batch("bf16", d=192, V=700, lens=[90, 500, 7, 64], n_groups=2, seed=51, beta=1.3)
+    want = [_run(b) for b in (ba, bb)]
+    torch.cuda.synchronize()
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    got = []
+    for b, st in zip((ba, bb), streams):
+        with torch.cuda.stream(st):
+            got.append(oapl.loss_fwd_bwd(b.H, b.W, b.tokens, b.logq, b.seq_offsets, b.rewards, b.group_ids,
+                                         b.n_groups, b.beta))
+    torch.cuda.synchronize()
+    for g, w in zip(got, want):
+        assert oapl.read_device_status(g.workspace) == 0
+        for x, y in ((g.loss, w.loss), (g.logprob, w.logprob), (g.dH, w.dH), (g.dW, w.dW)):
+            assert torch.equal(x, y)
