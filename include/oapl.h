@@ -26,8 +26,10 @@
  *     oapl_read_device_status.
  *   - Inputs are never modified; outputs are fully overwritten.
  *   - `workspace` must hold at least oapl_workspace_bytes(...) bytes for the
- *     same sizes, aligned to 256 bytes.  Its contents are scratch.  Two calls
- *     may run concurrently only with distinct workspaces.
+ *     same sizes, aligned to 256 bytes (the loss calls also accept less, see
+ *     oapl_workspace_bytes_for_panel).  Its contents are scratch.  Two calls
+ *     may run concurrently only with distinct workspaces.  The library keeps
+ *     no state between calls: there are no process-wide switches.
  *   - The return value is an oapl_status.  Errors the host can see (null
  *     pointers, bad sizes, bad beta, short workspace) return before anything
  *     is launched.  Errors in device data (token id outside [0, V), group id
@@ -71,16 +73,47 @@ const char* oapl_status_string(int32_t status);
 
 /*
  * Shape limits: T >= 0 (T == 0 is legal and yields loss = sum of squared
- * advantages), 1 <= d <= 2^21, 1 <= V <= 2^21, 0 <= n_seq, 1 <= n_groups.
- * OAPL_BF16 additionally needs d to be a multiple of 8 (16-byte rows) and
- * T <= 65535 * 256.  Anything else is OAPL_ERR_SHAPE.
+ * advantages), 1 <= d <= 2^21, 1 <= V <= 2^21, 0 <= n_seq, 1 <= n_groups,
+ * n_seq * n_groups <= 2^32 (each prompt's wavefront walks all rollouts to find
+ * its own).  OAPL_BF16 additionally needs d to be a multiple of 8 (16-byte
+ * rows) and T <= 65535 * 256; OAPL_F32 needs T <= 65535 * 64.  Anything else
+ * is OAPL_ERR_SHAPE.
  */
+
+/* Options of the loss entry points that take a `flags` argument (bit set). */
+typedef enum {
+  OAPL_FLAG_TWO_PASS = 1  /* never try the single sweep: log-sum-exp pass first, then soft-max recompute per panel */
+} oapl_flags;
 
 /* Bytes of workspace the two calls below need for these sizes (host call, no
  * GPU work).  with_backward = 0 sizes it for oapl_logprob_fwd and for
  * oapl_loss_fwd_bwd with dH = dW = NULL.  Returns 0 for invalid sizes. */
 size_t oapl_workspace_bytes(int64_t T, int32_t d, int32_t V, int32_t n_seq,
                             int32_t n_groups, int32_t dtype, int32_t with_backward);
+
+/*
+ * The workspace is the memory budget of a loss call.  The gradients are
+ * produced panel by panel (a panel = a range of token rows whose soft-max
+ * values are held, bf16, until the dH and dW contractions have consumed them),
+ * and nearly all of the workspace is panel storage, proportional to the panel's
+ * rows.  oapl_workspace_bytes sizes it for the library's default panel (the
+ * fastest: at most 61440 rows for OAPL_BF16, 4096 for OAPL_F32).  This call
+ * returns the bytes needed when panels are at most max_panel_rows rows
+ * (rounded down to whole 384-row tiles for OAPL_BF16, at least one tile;
+ * <= 0 or above the default = the default) and stores the panel size the plan
+ * then uses in *panel_rows_out (host pointer, may be NULL).
+ *
+ * A loss call handed a workspace smaller than oapl_workspace_bytes(...) uses
+ * the largest panel whose plan fits workspace_bytes, and fails with
+ * OAPL_ERR_WORKSPACE only if not even a one-tile panel fits.  Results do not
+ * depend on the panel size beyond rounding (summation order of dW over
+ * panels).  The single sweep additionally needs every rollout to be at most
+ * one panel long; with smaller panels and longer rollouts the call takes the
+ * two-pass schedule (decided on the device).
+ */
+size_t oapl_workspace_bytes_for_panel(int64_t T, int32_t d, int32_t V, int32_t n_seq,
+                                      int32_t n_groups, int32_t dtype, int32_t with_backward,
+                                      int64_t max_panel_rows, int64_t* panel_rows_out);
 
 /*
  * Per-token log-probability of the sampled token under pi (the ln pi(y_t | x,
@@ -149,7 +182,7 @@ int32_t oapl_sample_tokens(const void* H, const void* W, int64_t T, int32_t d, i
  *               dW[v,:] = sum_t c_t (1[v = y_t] - p_{t,v}) H[t,:]
  *
  * How the gradients are scheduled (bf16): the logits are visited ONCE.  Panels of
- * at most 61440 token rows are swept with the soft-max written unnormalised
+ * token rows (at most 61440, fewer if the workspace is smaller) are swept with the soft-max written unnormalised
  * (bf16, against a per-row reference exponent fixed before the sweep), their
  * row sums give lse and the log-probs, and the dH / dW contractions consume a
  * panel as soon as every rollout touching it is scored.  That needs (a) no
@@ -190,14 +223,16 @@ int32_t oapl_loss_fwd_bwd(const void* H, const void* W, const int32_t* tokens,
 
 /*
  * Same as oapl_loss_fwd_bwd with separate constants, as the experimental
- * section (Sec. 5) uses: beta_value in Eq. 2 and beta_loss in Eq. 3.
+ * section (Sec. 5) uses: beta_value in Eq. 2 and beta_loss in Eq. 3, and with
+ * per-call options: flags is 0 or a set of oapl_flags (unknown bits are
+ * OAPL_ERR_SHAPE).
  */
 int32_t oapl_loss_fwd_bwd_two_beta(const void* H, const void* W, const int32_t* tokens,
                                    const float* logq, const int64_t* seq_offsets,
                                    const float* rewards, const int32_t* group_ids,
                                    int64_t T, int32_t d, int32_t V, int32_t n_seq, int32_t n_groups,
                                    int32_t dtype, float beta_value, float beta_loss, float loss_scale,
-                                   float* loss_out, float* logprob_out, float* seq_logratio_out,
+                                   uint32_t flags, float* loss_out, float* logprob_out, float* seq_logratio_out,
                                    float* vstar_out, void* dH, float* dW,
                                    void* workspace, size_t workspace_bytes, void* stream);
 
@@ -219,14 +254,15 @@ int32_t oapl_loss_fwd_bwd_two_beta(const void* H, const void* W, const int32_t* 
  * deviation plus adv_eps is this library's reading.
  *   logp_old [T] float: log-probs of the tokens under the previous trainer policy
  *   0 <= clip_eps < 1, adv_eps >= 0, all finite (else OAPL_ERR_BETA)
- *   adv_out [n_seq] float or NULL; other arguments as for oapl_loss_fwd_bwd.
+ *   adv_out [n_seq] float or NULL; flags as for oapl_loss_fwd_bwd_two_beta; other
+ *   arguments as for oapl_loss_fwd_bwd.
  */
 int32_t oapl_grpo_loss_fwd_bwd(const void* H, const void* W, const int32_t* tokens,
                                const float* logq, const float* logp_old, const int64_t* seq_offsets,
                                const float* rewards, const int32_t* group_ids,
                                int64_t T, int32_t d, int32_t V, int32_t n_seq, int32_t n_groups,
                                int32_t dtype, float clip_eps, float adv_eps, float loss_scale,
-                               float* loss_out, float* logprob_out, float* adv_out,
+                               uint32_t flags, float* loss_out, float* logprob_out, float* adv_out,
                                void* dH, float* dW,
                                void* workspace, size_t workspace_bytes, void* stream);
 
@@ -250,12 +286,9 @@ int32_t oapl_read_device_status(const void* workspace, void* stream, int32_t* st
  * Which schedule the last loss call on `workspace` ended up using: waits for
  * `stream`, then *two_pass_out (host pointer) = 1 if the device sent the call
  * down the two-pass path, 0 if the single sweep was valid (also 0 for calls
- * that never try the sweep: fp32, forward-only, empty).
- * oapl_single_sweep_enable(0) makes later loss calls of the process skip the
- * single sweep altogether (two passes always); 1 restores the default.
+ * that never try the sweep: fp32, forward-only, empty, OAPL_FLAG_TWO_PASS).
  */
 int32_t oapl_read_path_taken(const void* workspace, void* stream, int32_t* two_pass_out);
-void oapl_single_sweep_enable(int32_t on);
 
 /*
  * Measurement aid, not part of the method.  The path's time is spent in the

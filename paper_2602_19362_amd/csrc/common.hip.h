@@ -41,6 +41,15 @@ constexpr int kErrTokenRange = 9;
 __device__ __forceinline__ void record_error(int* flag, int code) {
   atomicCAS(flag, 0, code);
 }
+// Errors in the batch structure (offsets, group ids) make the loss NaN whatever was recorded
+// first, so they are also kept in the status word behind the first.
+__device__ __forceinline__ void record_batch_error(int* flag, int code) {
+  atomicCAS(flag + 1, 0, code);
+  atomicCAS(flag, 0, code);
+}
+__device__ __forceinline__ bool batch_error(const int* flag) {
+  return __hip_atomic_load(flag + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0;
+}
 
 // A kernel launched with a gate runs only if the flag word's truth value equals
 // `want` (flag == nullptr: always runs).  The loss entry points use it to choose,

@@ -26,6 +26,7 @@ typedef TileCfg<4, 2, 2, 4, 2> CfgSample;
 
 constexpr int64_t kPanelBf16 = 61440;  // most token rows per backward panel (bf16 path): 160 token tiles
 constexpr int64_t kPanelF32 = 4096;    // ... (fp32 path)
+constexpr int64_t kGroupScanLimit = (int64_t)1 << 32;   // n_seq * n_groups: every prompt's wavefront walks all rollouts
 constexpr int kStatusWords = 64;       // 256-byte header
 constexpr int kNumCU = 256;            // MI355X compute units (one workgroup of the dense kernels each: it fills the LDS)
 
@@ -54,10 +55,17 @@ constexpr int kFlagWord = 8;   // status word that selects the two-pass path on 
 // they show in the gradient norm.  Smaller batches take the two-pass path, whose one-hot entry is exact.
 constexpr int64_t kSweepMinTokens = 64;
 
-// Process-wide switch for the single-sweep loss path (on by default).
-static bool g_single_sweep = true;
+// Largest panel the plan may use: `max_panel_rows` <= 0 means the library's default cap; other
+// values are rounded down to whole token tiles (bf16), with one tile as the least.
+static int64_t panel_cap(int dtype, int64_t max_panel_rows) {
+  const int64_t deflt = dtype == OAPL_BF16 ? kPanelBf16 : kPanelF32;
+  if (max_panel_rows <= 0 || max_panel_rows > deflt) return deflt;
+  if (dtype != OAPL_BF16) return max_panel_rows;
+  return max_panel_rows < Cfg::BN ? Cfg::BN : max_panel_rows / Cfg::BN * Cfg::BN;
+}
 
-static bool make_plan(Plan& p, int64_t T, int d, int V, int n_seq, int n_groups, int dtype, bool bwd) {
+static bool make_plan(Plan& p, int64_t T, int d, int V, int n_seq, int n_groups, int dtype, bool bwd,
+                      int64_t max_panel_rows = 0) {
   if (T < 0 || d < 1 || V < 1 || n_seq < 0 || n_groups < 1) return false;
   if (dtype != OAPL_F32 && dtype != OAPL_BF16) return false;
   if (dtype == OAPL_BF16 && (d % 8) != 0) return false;
@@ -65,6 +73,10 @@ static bool make_plan(Plan& p, int64_t T, int d, int V, int n_seq, int n_groups,
   // and the packing kernels index token tiles with gridDim.y
   if ((int64_t)d > (1 << 21) || (int64_t)V > (1 << 21)) return false;
   if (dtype == OAPL_BF16 && T > (int64_t)65535 * 256) return false;
+  // the fp32 kernels index 64-row token tiles with gridDim.y
+  if (dtype == OAPL_F32 && T > (int64_t)65535 * 64) return false;
+  if ((int64_t)n_seq * n_groups > kGroupScanLimit) return false;
+  const int64_t cap = panel_cap(dtype, max_panel_rows);
   p.T = T; p.d = d; p.V = V; p.n_seq = n_seq; p.n_groups = n_groups; p.dtype = dtype; p.bwd = bwd;
   if (dtype == OAPL_BF16) {
     const int64_t n_tiles = (T + Cfg::BN - 1) / Cfg::BN;
@@ -93,13 +105,13 @@ static bool make_plan(Plan& p, int64_t T, int d, int V, int n_seq, int n_groups,
     // the dH contraction -- its tiles (d / 256 x panel rows / 384, each K = V long) are few and long, so
     // a partly filled last round is expensive -- plus a charge per panel for the fp32 read-add-write
     // pass over dW.  Ties go to the larger panel (longer rollouts fit the single sweep).
-    if (T <= kPanelBf16) {
+    if (T <= cap) {
       p.Tp = round_up(T > 0 ? T : 1, Cfg::BN);
     } else {
       const int64_t mtd = (d + Cfg::BM - 1) / Cfg::BM;
-      const int64_t k_max = kPanelBf16 / Cfg::BN;
+      const int64_t k_max = cap / Cfg::BN;
       double best = 1e300;
-      for (int64_t k = k_max; k >= k_max / 2; --k) {
+      for (int64_t k = k_max; k >= (k_max + 1) / 2; --k) {
         const int64_t rows = k * Cfg::BN;
         const int64_t full = T / rows, rest = T - full * rows;
         const int64_t rounds_full = (mtd * k + kNumCU - 1) / kNumCU;
@@ -118,7 +130,7 @@ static bool make_plan(Plan& p, int64_t T, int d, int V, int n_seq, int n_groups,
     p.n_kt_t = (int)(p.Tp / kPackK);                 // strips whose k index is the panel token
   } else {
     p.n_parts = p.n_parts_s = (V + 63) / 64;
-    p.Tp = T < kPanelF32 ? (T > 0 ? T : 1) : kPanelF32;
+    p.Tp = T < cap ? (T > 0 ? T : 1) : cap;
   }
   size_t o = 0;
   auto take = [&](size_t bytes) { size_t at = o; o += (bytes + 255) / 256 * 256; return at; };
@@ -491,12 +503,32 @@ static int check_workspace(const void* ws, size_t have, size_t need) {
   return OAPL_OK;
 }
 
+// The plan of a loss call: the workspace the caller hands over is the budget.  The default plan
+// if it fits; otherwise the largest backward panel (whole token tiles for bf16) whose plan does.
+static int fit_plan(Plan& p, int64_t T, int d, int V, int n_seq, int n_groups, int dtype, bool bwd, const void* ws,
+                    size_t have) {
+  if (!make_plan(p, T, d, V, n_seq, n_groups, dtype, bwd)) return OAPL_ERR_SHAPE;
+  if (ws == nullptr || ((uintptr_t)ws & 255) != 0) return OAPL_ERR_WORKSPACE;
+  if (p.total <= have) return OAPL_OK;
+  if (!bwd) return OAPL_ERR_WORKSPACE;
+  const int64_t step = dtype == OAPL_BF16 ? Cfg::BN : 64;
+  for (int64_t rows = (p.Tp - 1) / step * step; rows >= step; rows -= step) {
+    Plan q;
+    if (make_plan(q, T, d, V, n_seq, n_groups, dtype, bwd, rows) && q.total <= have) {
+      p = q;
+      return OAPL_OK;
+    }
+  }
+  return OAPL_ERR_WORKSPACE;
+}
+
 static int loss_impl(const void* H, const void* W, const int32_t* tokens, const float* logq,
                      const int64_t* seq_offsets, const float* rewards, const int32_t* group_ids, int64_t T, int32_t d,
                      int32_t V, int32_t n_seq, int32_t n_groups, int32_t dtype, float beta_value, float beta_loss,
-                     float loss_scale, float* loss_out, float* logprob_out, float* seq_logratio_out, float* vstar_out,
-                     void* dH, float* dW, void* workspace, size_t workspace_bytes, void* stream) {
+                     float loss_scale, uint32_t flags, float* loss_out, float* logprob_out, float* seq_logratio_out,
+                     float* vstar_out, void* dH, float* dW, void* workspace, size_t workspace_bytes, void* stream) {
   if (dtype != OAPL_F32 && dtype != OAPL_BF16) return OAPL_ERR_DTYPE;
+  if (flags & ~(uint32_t)OAPL_FLAG_TWO_PASS) return OAPL_ERR_SHAPE;
   const bool bwd = (dH != nullptr) || (dW != nullptr);
   Plan p;
   if (!make_plan(p, T, d, V, n_seq, n_groups, dtype, bwd)) return OAPL_ERR_SHAPE;
@@ -507,7 +539,7 @@ static int loss_impl(const void* H, const void* W, const int32_t* tokens, const 
   if (!(beta_value > 0.f) || !(beta_loss > 0.f) || !isfinite(beta_value) || !isfinite(beta_loss) ||
       !isfinite(loss_scale))
     return OAPL_ERR_BETA;
-  if (int rc = check_workspace(workspace, workspace_bytes, p.total)) return rc;
+  if (int rc = fit_plan(p, T, d, V, n_seq, n_groups, dtype, bwd, workspace, workspace_bytes)) return rc;
 
   hipStream_t st = (hipStream_t)stream;
   char* ws = (char*)workspace;
@@ -524,10 +556,9 @@ static int loss_impl(const void* H, const void* W, const int32_t* tokens, const 
                                                      gate);
       OAPL_LAUNCH_CHECK();
     }
-    k_group_value_loss<<<1, 256, 0, st>>>(Delta, rewards, group_ids, seq_offsets, n_seq, n_groups, T,
-                                          (double)beta_value, (double)beta_loss, (double)loss_scale,
-                                          (double*)(ws + p.off_vstar), cseq, loss_out, seq_logratio_out, vstar_out,
-                                          status, gate);
+    k_residual_loss<<<1, 256, 0, st>>>(Delta, rewards, group_ids, seq_offsets, n_seq, n_groups, T,
+                                       (double)beta_loss, (double)loss_scale, (const double*)(ws + p.off_vstar), cseq,
+                                       loss_out, seq_logratio_out, status, gate);
     OAPL_LAUNCH_CHECK();
     if (bwd && T > 0) {
       k_fill_f32<<<grid1d(T, 256 * 8), 256, 0, st>>>(coef, T, 0.f, gate);
@@ -541,9 +572,13 @@ static int loss_impl(const void* H, const void* W, const int32_t* tokens, const 
   };
 
   if (int rc = prepare_operands(p, H, W, tokens, ws, st)) return rc;
+  // Eq. 2 needs the rewards only: one wavefront per prompt, before anything is scored
+  k_group_value<<<grid1d(n_groups, 4), 256, 0, st>>>(rewards, group_ids, n_seq, n_groups, (double)beta_value,
+                                                     (double*)(ws + p.off_vstar), vstar_out, status, kNoGate);
+  OAPL_LAUNCH_CHECK();
   // bf16 with gradients: one sweep over the logits; the two-pass path behind it runs only if the
   // sweep's preconditions fail on this call's data (decided on the device, in stream order)
-  const bool sweep = bwd && T >= kSweepMinTokens && p.sweep && g_single_sweep;
+  const bool sweep = bwd && T >= kSweepMinTokens && p.sweep && !(flags & OAPL_FLAG_TWO_PASS);
   Gate slow = kNoGate;
   if (sweep) {
     if (int rc = sweep_path(p, H, W, tokens, logq, seq_offsets, logprob_out, dH, dW, ws, st, objective)) return rc;
@@ -561,9 +596,10 @@ static int loss_impl(const void* H, const void* W, const int32_t* tokens, const 
 static int grpo_impl(const void* H, const void* W, const int32_t* tokens, const float* logq, const float* logp_old,
                      const int64_t* seq_offsets, const float* rewards, const int32_t* group_ids, int64_t T, int32_t d,
                      int32_t V, int32_t n_seq, int32_t n_groups, int32_t dtype, float clip_eps, float adv_eps,
-                     float loss_scale, float* loss_out, float* logprob_out, float* adv_out, void* dH, float* dW,
-                     void* workspace, size_t workspace_bytes, void* stream) {
+                     float loss_scale, uint32_t flags, float* loss_out, float* logprob_out, float* adv_out, void* dH,
+                     float* dW, void* workspace, size_t workspace_bytes, void* stream) {
   if (dtype != OAPL_F32 && dtype != OAPL_BF16) return OAPL_ERR_DTYPE;
+  if (flags & ~(uint32_t)OAPL_FLAG_TWO_PASS) return OAPL_ERR_SHAPE;
   const bool bwd = (dH != nullptr) || (dW != nullptr);
   Plan p;
   if (!make_plan(p, T, d, V, n_seq, n_groups, dtype, bwd)) return OAPL_ERR_SHAPE;
@@ -572,7 +608,7 @@ static int grpo_impl(const void* H, const void* W, const int32_t* tokens, const 
   if (n_seq > 0 && (!rewards || !group_ids)) return OAPL_ERR_NULL;
   if (!(clip_eps >= 0.f) || !(clip_eps < 1.f) || !(adv_eps >= 0.f) || !isfinite(adv_eps) || !isfinite(loss_scale))
     return OAPL_ERR_BETA;
-  if (int rc = check_workspace(workspace, workspace_bytes, p.total)) return rc;
+  if (int rc = fit_plan(p, T, d, V, n_seq, n_groups, dtype, bwd, workspace, workspace_bytes)) return rc;
 
   hipStream_t st = (hipStream_t)stream;
   char* ws = (char*)workspace;
@@ -593,17 +629,21 @@ static int grpo_impl(const void* H, const void* W, const int32_t* tokens, const 
                                            adv, wseq, (double)clip_eps, factor, coef, seqterm, gate);
       OAPL_LAUNCH_CHECK();
     }
-    k_grpo_loss<<<1, 64, 0, st>>>(seqterm, n_seq, status, loss_out, gate);
+    k_grpo_loss<<<1, 256, 0, st>>>(seqterm, n_seq, status, loss_out, gate);
     OAPL_LAUNCH_CHECK();
     return OAPL_OK;
   };
 
   if (int rc = prepare_operands(p, H, W, tokens, ws, st)) return rc;
-  k_grpo_advantage<<<1, 256, 0, st>>>(rewards, group_ids, seq_offsets, n_seq, n_groups, T, (double)adv_eps,
-                                      (double)loss_scale, gstat, gstat + n_groups, adv, wseq, adv_out, status,
-                                      kNoGate);
+  k_grpo_group_stats<<<grid1d(n_groups, 4), 256, 0, st>>>(rewards, group_ids, n_seq, n_groups, gstat,
+                                                          gstat + n_groups, wseq + (n_seq > 0 ? n_seq : 1), status,
+                                                          kNoGate);
   OAPL_LAUNCH_CHECK();
-  const bool sweep = bwd && T >= kSweepMinTokens && p.sweep && g_single_sweep;
+  k_grpo_advantage<<<grid1d(n_seq > 0 ? n_seq : 1, 256), 256, 0, st>>>(
+      rewards, group_ids, seq_offsets, n_seq, n_groups, T, (double)adv_eps, (double)loss_scale, gstat,
+      gstat + n_groups, wseq + (n_seq > 0 ? n_seq : 1), adv, wseq, adv_out, status, kNoGate);
+  OAPL_LAUNCH_CHECK();
+  const bool sweep = bwd && T >= kSweepMinTokens && p.sweep && !(flags & OAPL_FLAG_TWO_PASS);
   Gate slow = kNoGate;
   if (sweep) {
     if (int rc = sweep_path(p, H, W, tokens, logq, seq_offsets, logprob_out, dH, dW, ws, st, objective)) return rc;
@@ -642,6 +682,15 @@ size_t oapl_workspace_bytes(int64_t T, int32_t d, int32_t V, int32_t n_seq, int3
                             int32_t with_backward) {
   Plan p;
   if (!make_plan(p, T, d, V, n_seq, n_groups, dtype, with_backward != 0)) return 0;
+  return p.total;
+}
+
+size_t oapl_workspace_bytes_for_panel(int64_t T, int32_t d, int32_t V, int32_t n_seq, int32_t n_groups,
+                                      int32_t dtype, int32_t with_backward, int64_t max_panel_rows,
+                                      int64_t* panel_rows_out) {
+  Plan p;
+  if (!make_plan(p, T, d, V, n_seq, n_groups, dtype, with_backward != 0, max_panel_rows)) return 0;
+  if (panel_rows_out) *panel_rows_out = p.Tp;
   return p.total;
 }
 
@@ -712,18 +761,18 @@ int32_t oapl_loss_fwd_bwd(const void* H, const void* W, const int32_t* tokens, c
                           float* vstar_out, void* dH, float* dW, void* workspace, size_t workspace_bytes,
                           void* stream) {
   return loss_impl(H, W, tokens, logq, seq_offsets, rewards, group_ids, T, d, V, n_seq, n_groups, dtype, beta, beta,
-                   loss_scale, loss_out, logprob_out, seq_logratio_out, vstar_out, dH, dW, workspace,
+                   loss_scale, 0u, loss_out, logprob_out, seq_logratio_out, vstar_out, dH, dW, workspace,
                    workspace_bytes, stream);
 }
 
 int32_t oapl_loss_fwd_bwd_two_beta(const void* H, const void* W, const int32_t* tokens, const float* logq,
                                    const int64_t* seq_offsets, const float* rewards, const int32_t* group_ids,
                                    int64_t T, int32_t d, int32_t V, int32_t n_seq, int32_t n_groups, int32_t dtype,
-                                   float beta_value, float beta_loss, float loss_scale, float* loss_out,
-                                   float* logprob_out, float* seq_logratio_out, float* vstar_out, void* dH, float* dW,
-                                   void* workspace, size_t workspace_bytes, void* stream) {
+                                   float beta_value, float beta_loss, float loss_scale, uint32_t flags,
+                                   float* loss_out, float* logprob_out, float* seq_logratio_out, float* vstar_out,
+                                   void* dH, float* dW, void* workspace, size_t workspace_bytes, void* stream) {
   return loss_impl(H, W, tokens, logq, seq_offsets, rewards, group_ids, T, d, V, n_seq, n_groups, dtype, beta_value,
-                   beta_loss, loss_scale, loss_out, logprob_out, seq_logratio_out, vstar_out, dH, dW, workspace,
+                   beta_loss, loss_scale, flags, loss_out, logprob_out, seq_logratio_out, vstar_out, dH, dW, workspace,
                    workspace_bytes, stream);
 }
 
@@ -731,10 +780,10 @@ int32_t oapl_grpo_loss_fwd_bwd(const void* H, const void* W, const int32_t* toke
                                const float* logp_old, const int64_t* seq_offsets, const float* rewards,
                                const int32_t* group_ids, int64_t T, int32_t d, int32_t V, int32_t n_seq,
                                int32_t n_groups, int32_t dtype, float clip_eps, float adv_eps, float loss_scale,
-                               float* loss_out, float* logprob_out, float* adv_out, void* dH, float* dW,
-                               void* workspace, size_t workspace_bytes, void* stream) {
+                               uint32_t flags, float* loss_out, float* logprob_out, float* adv_out, void* dH,
+                               float* dW, void* workspace, size_t workspace_bytes, void* stream) {
   return grpo_impl(H, W, tokens, logq, logp_old, seq_offsets, rewards, group_ids, T, d, V, n_seq, n_groups, dtype,
-                   clip_eps, adv_eps, loss_scale, loss_out, logprob_out, adv_out, dH, dW, workspace, workspace_bytes,
+                   clip_eps, adv_eps, loss_scale, flags, loss_out, logprob_out, adv_out, dH, dW, workspace, workspace_bytes,
                    stream);
 }
 
@@ -777,8 +826,6 @@ int32_t oapl_timing_read(int32_t kernel, double* total_ms, int64_t* launches) {
   *launches = (int64_t)t.ev[kernel].size();
   return OAPL_OK;
 }
-
-void oapl_single_sweep_enable(int32_t on) { g_single_sweep = on != 0; }
 
 int32_t oapl_read_path_taken(const void* workspace, void* stream, int32_t* two_pass_out) {
   if (!workspace || !two_pass_out) return OAPL_ERR_NULL;

@@ -142,59 +142,87 @@ k_segmented_sum(const T* __restrict__ x, const int64_t* __restrict__ off, int n_
   if (threadIdx.x == 0) out[s] = ((wsum[0] + wsum[1]) + wsum[2]) + wsum[3];
 }
 
-// Group value estimate, residuals and loss (one workgroup; N and P are small).
-//   V*_g    = beta_v ln( (1/G_g) sum_{s in g} exp(r_s / beta_v) )            Eq. 2
-//           = m_g + beta_v ln( (1/G_g) sum exp((r_s - m_g) / beta_v) ),  m_g = max_{s in g} r_s
-//             (same value; the shift keeps exp() in range for small beta and
-//             makes all-equal rewards return exactly r)
+// Butterfly reductions over a wavefront: every lane ends with the same value, combined in a
+// fixed order (bit-reproducible).
+__device__ __forceinline__ double wave_allsum(double v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+__device__ __forceinline__ double wave_allmax(double v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmax(v, __shfl_xor(v, o, 64));
+  return v;
+}
+__device__ __forceinline__ int wave_allsum(int v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+
+// Group value estimate, one wavefront per prompt (4 prompts per workgroup):
+//   V*_g = beta_v ln( (1/G_g) sum_{s in g} exp(r_s / beta_v) )            Eq. 2
+//        = m_g + beta_v ln( (1/G_g) sum exp((r_s - m_g) / beta_v) ),  m_g = max_{s in g} r_s
+// (same value; the shift keeps exp() in range for small beta and makes all-equal rewards return
+// exactly r).  Group ids come in any order, so the wavefront walks the rollouts lane-strided and
+// keeps those of its prompt: lane-local partial max / count / sum in rollout order, then shuffle
+// butterflies.  A prompt without rollouts gets NaN and records the group error.
+__global__ void __launch_bounds__(256)
+k_group_value(const float* __restrict__ rewards, const int32_t* __restrict__ gid, int n_seq, int n_groups,
+              double beta_v, double* __restrict__ vstar_ws, float* __restrict__ vstar_out, int* __restrict__ err,
+              Gate gate) {
+  if (gate_closed(gate)) return;
+  const int lane = threadIdx.x & 63;
+  const int g = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (g >= n_groups) return;
+  double m = -1.0e300;
+  int cnt = 0;
+  for (int s = lane; s < n_seq; s += 64)
+    if (gid[s] == g) { m = fmax(m, (double)rewards[s]); ++cnt; }
+  m = wave_allmax(m);
+  cnt = wave_allsum(cnt);
+  double v;
+  if (cnt == 0) {
+    if (lane == 0) record_batch_error(err, kErrGroup);
+    v = __builtin_nan("");
+  } else {
+    double sum = 0.0;
+    for (int s = lane; s < n_seq; s += 64)
+      if (gid[s] == g) sum += exp(((double)rewards[s] - m) / beta_v);
+    sum = wave_allsum(sum);
+    v = m + beta_v * log(sum / (double)cnt);
+  }
+  if (lane == 0) {
+    vstar_ws[g] = v;
+    if (vstar_out) vstar_out[g] = (float)v;
+  }
+}
+
+// Residuals and loss (one workgroup walks the rollouts; fixed summation order):
 //   delta_s = beta_l Delta_s - (r_s - V*_{g(s)})
 //   loss    = scale sum_s delta_s^2                                           Eq. 3
 //   cseq_s  = scale 2 beta_l delta_s      (d loss / d ln pi(y_t) for every token of s)
-// Also validates offsets and group ids; on a violation the loss is NaN and the
-// status word is set.
+// Also validates offsets and group ids; on a violation (or an empty prompt found by
+// k_group_value, whose V* is NaN) the loss is NaN and the status word is set.
 __global__ void __launch_bounds__(256)
-k_group_value_loss(const double* __restrict__ Delta, const float* __restrict__ rewards,
-                   const int32_t* __restrict__ gid, const int64_t* __restrict__ off, int n_seq, int n_groups,
-                   int64_t Ttok, double beta_v, double beta_l, double scale, double* __restrict__ vstar_ws,
-                   float* __restrict__ cseq, float* __restrict__ loss_out, float* __restrict__ seq_logratio_out,
-                   float* __restrict__ vstar_out, int* __restrict__ err, Gate gate) {
+k_residual_loss(const double* __restrict__ Delta, const float* __restrict__ rewards,
+                const int32_t* __restrict__ gid, const int64_t* __restrict__ off, int n_seq, int n_groups,
+                int64_t Ttok, double beta_l, double scale, const double* __restrict__ vstar_ws,
+                float* __restrict__ cseq, float* __restrict__ loss_out, float* __restrict__ seq_logratio_out,
+                int* __restrict__ err, Gate gate) {
   __shared__ double wsum[4];
   __shared__ int bad;
   if (gate_closed(gate)) return;
   const int tid = threadIdx.x;
-  if (tid == 0) bad = 0;
+  if (tid == 0) bad = (off[0] != 0 || off[n_seq] != Ttok) ? kErrOffsets : 0;
   __syncthreads();
-
-  if (tid == 0 && (off[0] != 0 || off[n_seq] != Ttok)) { bad = kErrOffsets; }
-  for (int s = tid; s < n_seq; s += 256) {
-    if (off[s + 1] < off[s]) atomicCAS(&bad, 0, kErrOffsets);
-    if (gid[s] < 0 || gid[s] >= n_groups) atomicCAS(&bad, 0, kErrGroup);
-  }
-  for (int g = tid; g < n_groups; g += 256) {
-    double m = -1.0e300;
-    int cnt = 0;
-    for (int s = 0; s < n_seq; ++s)
-      if (gid[s] == g) { m = fmax(m, (double)rewards[s]); ++cnt; }
-    double v = 0.0;
-    if (cnt == 0) {
-      atomicCAS(&bad, 0, kErrGroup);
-      v = __builtin_nan("");
-    } else {
-      double sum = 0.0;
-      for (int s = 0; s < n_seq; ++s)
-        if (gid[s] == g) sum += exp(((double)rewards[s] - m) / beta_v);
-      v = m + beta_v * log(sum / (double)cnt);
-    }
-    vstar_ws[g] = v;
-    if (vstar_out) vstar_out[g] = (float)v;
-  }
-  __threadfence_block();
-  __syncthreads();
-
   double acc = 0.0;
   for (int s = tid; s < n_seq; s += 256) {
+    if (off[s + 1] < off[s]) atomicCAS(&bad, 0, kErrOffsets);
     const int g = gid[s];
-    const double v = (g >= 0 && g < n_groups) ? vstar_ws[g] : __builtin_nan("");
+    const bool g_ok = g >= 0 && g < n_groups;
+    if (!g_ok) atomicCAS(&bad, 0, kErrGroup);
+    const double v = g_ok ? vstar_ws[g] : __builtin_nan("");
     const double delta = beta_l * Delta[s] - ((double)rewards[s] - v);
     cseq[s] = (float)(scale * 2.0 * beta_l * delta);
     if (seq_logratio_out) seq_logratio_out[s] = (float)Delta[s];
@@ -205,64 +233,73 @@ k_group_value_loss(const double* __restrict__ Delta, const float* __restrict__ r
   __syncthreads();
   if (tid == 0) {
     double loss = scale * (((wsum[0] + wsum[1]) + wsum[2]) + wsum[3]);
-    if (bad) {
-      loss = __builtin_nan("");
-      record_error(err, bad);
-    }
+    if (bad) record_batch_error(err, bad);
+    if (batch_error(err)) loss = __builtin_nan("");
     loss_out[0] = (float)loss;
   }
 }
 
-// GRPO baseline (Sec. 2, the displayed GRPO objective), group step: the normalised advantage
-//   A_s = (r_s - mean_g r) / (std_g r + adv_eps)     (population standard deviation of the group)
-// and the weight w_s = scale / (G_g |y_s|) of rollout s (0 for an empty rollout).  One workgroup;
-// validates offsets and group ids like the OAPL kernel and records the status.
+// GRPO baseline (Sec. 2, the displayed GRPO objective), group step, one wavefront per prompt:
+// mean and population standard deviation of the prompt's rewards and its size G_g (kept behind
+// the per-rollout weights).  A prompt without rollouts gets NaN and records the group error.
 __global__ void __launch_bounds__(256)
-k_grpo_advantage(const float* __restrict__ rewards, const int32_t* __restrict__ gid, const int64_t* __restrict__ off,
-                 int n_seq, int n_groups, int64_t Ttok, double adv_eps, double scale, double* __restrict__ gmean,
-                 double* __restrict__ gstd, float* __restrict__ adv, double* __restrict__ wseq,
-                 float* __restrict__ adv_out, int* __restrict__ err, Gate gate) {
-  __shared__ int bad;
+k_grpo_group_stats(const float* __restrict__ rewards, const int32_t* __restrict__ gid, int n_seq, int n_groups,
+                   double* __restrict__ gmean, double* __restrict__ gstd, double* __restrict__ gsize,
+                   int* __restrict__ err, Gate gate) {
   if (gate_closed(gate)) return;
-  const int tid = threadIdx.x;
-  if (tid == 0) bad = 0;
-  __syncthreads();
-  if (tid == 0 && (off[0] != 0 || off[n_seq] != Ttok)) atomicCAS(&bad, 0, kErrOffsets);
-  for (int s = tid; s < n_seq; s += 256) {
-    if (off[s + 1] < off[s]) atomicCAS(&bad, 0, kErrOffsets);
-    if (gid[s] < 0 || gid[s] >= n_groups) atomicCAS(&bad, 0, kErrGroup);
-  }
-  for (int g = tid; g < n_groups; g += 256) {
-    double sum = 0.0;
-    int cnt = 0;
-    for (int s = 0; s < n_seq; ++s)
-      if (gid[s] == g) { sum += (double)rewards[s]; ++cnt; }
-    if (cnt == 0) {
-      atomicCAS(&bad, 0, kErrGroup);
+  const int lane = threadIdx.x & 63;
+  const int g = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (g >= n_groups) return;
+  double sum = 0.0;
+  int cnt = 0;
+  for (int s = lane; s < n_seq; s += 64)
+    if (gid[s] == g) { sum += (double)rewards[s]; ++cnt; }
+  sum = wave_allsum(sum);
+  cnt = wave_allsum(cnt);
+  if (cnt == 0) {
+    if (lane == 0) {
+      record_batch_error(err, kErrGroup);
       gmean[g] = __builtin_nan("");
       gstd[g] = __builtin_nan("");
-      continue;
+      gsize[g] = 0.0;
     }
-    const double mean = sum / cnt;
-    double var = 0.0;
-    for (int s = 0; s < n_seq; ++s)
-      if (gid[s] == g) { const double dlt = (double)rewards[s] - mean; var += dlt * dlt; }
+    return;
+  }
+  const double mean = sum / cnt;
+  double var = 0.0;
+  for (int s = lane; s < n_seq; s += 64)
+    if (gid[s] == g) { const double dlt = (double)rewards[s] - mean; var += dlt * dlt; }
+  var = wave_allsum(var);
+  if (lane == 0) {
     gmean[g] = mean;
     gstd[g] = sqrt(var / cnt);
-    wseq[n_seq + g] = (double)cnt;   // group sizes live behind the per-rollout weights
+    gsize[g] = (double)cnt;
   }
-  __threadfence_block();
-  __syncthreads();
-  for (int s = tid; s < n_seq; s += 256) {
+}
+
+// GRPO, rollout step: the normalised advantage
+//   A_s = (r_s - mean_g r) / (std_g r + adv_eps)
+// and the weight w_s = scale / (G_g |y_s|) of rollout s (0 for an empty rollout).  Validates
+// offsets and group ids like the OAPL kernel and records the status.
+__global__ void __launch_bounds__(256)
+k_grpo_advantage(const float* __restrict__ rewards, const int32_t* __restrict__ gid, const int64_t* __restrict__ off,
+                 int n_seq, int n_groups, int64_t Ttok, double adv_eps, double scale,
+                 const double* __restrict__ gmean, const double* __restrict__ gstd, const double* __restrict__ gsize,
+                 float* __restrict__ adv, double* __restrict__ wseq, float* __restrict__ adv_out,
+                 int* __restrict__ err, Gate gate) {
+  if (gate_closed(gate)) return;
+  if (blockIdx.x == 0 && threadIdx.x == 0 && (off[0] != 0 || off[n_seq] != Ttok)) record_batch_error(err, kErrOffsets);
+  for (int s = blockIdx.x * 256 + threadIdx.x; s < n_seq; s += gridDim.x * 256) {
+    if (off[s + 1] < off[s]) record_batch_error(err, kErrOffsets);
     const int g = gid[s];
-    const bool ok = g >= 0 && g < n_groups && !bad;
+    const bool ok = g >= 0 && g < n_groups;
+    if (!ok) record_batch_error(err, kErrGroup);
     const double a = ok ? ((double)rewards[s] - gmean[g]) / (gstd[g] + adv_eps) : __builtin_nan("");
     const int64_t len = off[s + 1] - off[s];
     adv[s] = (float)a;
     if (adv_out) adv_out[s] = (float)a;
-    wseq[s] = (ok && len > 0) ? scale / (wseq[n_seq + g] * (double)len) : 0.0;
+    wseq[s] = (ok && len > 0 && gsize[g] > 0.0) ? scale / (gsize[g] * (double)len) : 0.0;
   }
-  if (tid == 0 && bad) record_error(err, bad);
 }
 
 // GRPO, token step: one workgroup per rollout.  With r_t = pi / pi_old and IS_t = pi_old / pi_vllm,
@@ -300,15 +337,22 @@ k_grpo_tokens(const double* __restrict__ diff, const float* __restrict__ logq, c
   if (threadIdx.x == 0) seqterm[s] = -w * (((wsum[0] + wsum[1]) + wsum[2]) + wsum[3]);
 }
 
-// loss = sum_s seqterm[s] in rollout order (one thread: n_seq is small), NaN if a data error was recorded.
-__global__ void k_grpo_loss(const double* __restrict__ seqterm, int n_seq, const int* __restrict__ err,
-                            float* __restrict__ loss_out, Gate gate) {
+// loss = sum_s seqterm[s] (one workgroup, fixed order), NaN if an offsets / group error was recorded.
+__global__ void __launch_bounds__(256)
+k_grpo_loss(const double* __restrict__ seqterm, int n_seq, const int* __restrict__ err,
+            float* __restrict__ loss_out, Gate gate) {
+  __shared__ double wsum[4];
   if (gate_closed(gate)) return;
-  if (threadIdx.x != 0 || blockIdx.x != 0) return;
-  double loss = 0.0;
-  for (int s = 0; s < n_seq; ++s) loss += seqterm[s];
-  if (*err == kErrOffsets || *err == kErrGroup) loss = __builtin_nan("");
-  loss_out[0] = (float)loss;
+  double acc = 0.0;
+  for (int s = threadIdx.x; s < n_seq; s += 256) acc += seqterm[s];
+  acc = wave_sum(acc);
+  if ((threadIdx.x & 63) == 0) wsum[threadIdx.x >> 6] = acc;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    double loss = ((wsum[0] + wsum[1]) + wsum[2]) + wsum[3];
+    if (batch_error(err)) loss = __builtin_nan("");
+    loss_out[0] = (float)loss;
+  }
 }
 
 // coef[t] = cseq[s(t)] (times factor[t] if given): one workgroup per rollout

@@ -18,6 +18,7 @@ _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), _LIB_NAME)
 
 OAPL_F32 = 0
 OAPL_BF16 = 1
+OAPL_FLAG_TWO_PASS = 1
 
 STATUS_NAMES = {
     0: "OAPL_OK", 1: "OAPL_ERR_NULL", 2: "OAPL_ERR_SHAPE", 3: "OAPL_ERR_DTYPE", 4: "OAPL_ERR_OFFSETS",
@@ -30,6 +31,8 @@ _SIGNATURES = {
     "oapl_status_string": (_c.c_char_p, [_c.c_int32]),
     "oapl_workspace_bytes": (_c.c_size_t, [_c.c_int64, _c.c_int32, _c.c_int32, _c.c_int32, _c.c_int32, _c.c_int32,
                                            _c.c_int32]),
+    "oapl_workspace_bytes_for_panel": (_c.c_size_t, [_c.c_int64, _c.c_int32, _c.c_int32, _c.c_int32, _c.c_int32,
+                                                     _c.c_int32, _c.c_int32, _c.c_int64, _c.POINTER(_c.c_int64)]),
     "oapl_logprob_fwd": (_c.c_int32, [_c.c_void_p, _c.c_void_p, _c.c_void_p, _c.c_int64, _c.c_int32, _c.c_int32,
                                       _c.c_int32, _c.c_void_p, _c.c_void_p, _c.c_void_p, _c.c_void_p, _c.c_size_t,
                                       _c.c_void_p]),
@@ -39,13 +42,12 @@ _SIGNATURES = {
     "oapl_loss_fwd_bwd": (_c.c_int32, [_c.c_void_p] * 7 + [_c.c_int64] + [_c.c_int32] * 5 + [_c.c_float] * 2 +
                           [_c.c_void_p] * 7 + [_c.c_size_t, _c.c_void_p]),
     "oapl_loss_fwd_bwd_two_beta": (_c.c_int32, [_c.c_void_p] * 7 + [_c.c_int64] + [_c.c_int32] * 5 + [_c.c_float] * 3 +
-                                   [_c.c_void_p] * 7 + [_c.c_size_t, _c.c_void_p]),
+                                   [_c.c_uint32] + [_c.c_void_p] * 7 + [_c.c_size_t, _c.c_void_p]),
     "oapl_grpo_loss_fwd_bwd": (_c.c_int32, [_c.c_void_p] * 8 + [_c.c_int64] + [_c.c_int32] * 5 + [_c.c_float] * 3 +
-                               [_c.c_void_p] * 6 + [_c.c_size_t, _c.c_void_p]),
+                               [_c.c_uint32] + [_c.c_void_p] * 6 + [_c.c_size_t, _c.c_void_p]),
     "oapl_segmented_sum_f32": (_c.c_int32, [_c.c_void_p, _c.c_void_p, _c.c_int32, _c.c_void_p, _c.c_void_p]),
     "oapl_read_device_status": (_c.c_int32, [_c.c_void_p, _c.c_void_p, _c.POINTER(_c.c_int32)]),
     "oapl_read_path_taken": (_c.c_int32, [_c.c_void_p, _c.c_void_p, _c.POINTER(_c.c_int32)]),
-    "oapl_single_sweep_enable": (None, [_c.c_int32]),
     "oapl_timing_enable": (_c.c_int32, [_c.c_int32]),
     "oapl_timing_read": (_c.c_int32, [_c.c_int32, _c.POINTER(_c.c_double), _c.POINTER(_c.c_int64)]),
 }
@@ -111,8 +113,21 @@ def _stream(device) -> int:
     return torch.cuda.current_stream(device).cuda_stream
 
 
-def workspace_bytes(T: int, d: int, V: int, n_seq: int, n_groups: int, dtype: int, with_backward: bool) -> int:
-    return int(lib().oapl_workspace_bytes(T, d, V, n_seq, n_groups, dtype, 1 if with_backward else 0))
+def workspace_bytes(T: int, d: int, V: int, n_seq: int, n_groups: int, dtype: int, with_backward: bool,
+                    max_panel_rows: Optional[int] = None) -> int:
+    """oapl_workspace_bytes, or oapl_workspace_bytes_for_panel when a panel cap is given."""
+    if max_panel_rows is None:
+        return int(lib().oapl_workspace_bytes(T, d, V, n_seq, n_groups, dtype, 1 if with_backward else 0))
+    return workspace_bytes_for_panel(T, d, V, n_seq, n_groups, dtype, with_backward, max_panel_rows)[0]
+
+
+def workspace_bytes_for_panel(T: int, d: int, V: int, n_seq: int, n_groups: int, dtype: int, with_backward: bool,
+                              max_panel_rows: int):
+    """oapl_workspace_bytes_for_panel: (bytes, panel rows the plan uses)."""
+    rows = ctypes.c_int64(0)
+    n = lib().oapl_workspace_bytes_for_panel(T, d, V, n_seq, n_groups, dtype, 1 if with_backward else 0,
+                                             int(max_panel_rows), ctypes.byref(rows))
+    return int(n), int(rows.value)
 
 
 def _workspace(nbytes: int, device, workspace: Optional[torch.Tensor]) -> torch.Tensor:
@@ -140,9 +155,13 @@ def took_two_passes(workspace: torch.Tensor) -> bool:
     return bool(out.value)
 
 
-def single_sweep_enable(on: bool) -> None:
-    """oapl_single_sweep_enable: process-wide switch of the single-sweep loss schedule (default on)."""
-    lib().oapl_single_sweep_enable(1 if on else 0)
+def _check_device(t: torch.Tensor) -> None:
+    """The C ABI works on the current HIP device: the inputs must live there."""
+    if not t.is_cuda:
+        raise ValueError("inputs must be device tensors (there is no CPU path)")
+    if t.device.index != torch.cuda.current_device():
+        raise ValueError(f"inputs live on {t.device} but the current device is cuda:{torch.cuda.current_device()}; "
+                         "wrap the call in torch.cuda.device(...)")
 
 
 def logprob_fwd(H: torch.Tensor, W: torch.Tensor, tokens: torch.Tensor, *, want_lse: bool = False,
@@ -152,6 +171,7 @@ def logprob_fwd(H: torch.Tensor, W: torch.Tensor, tokens: torch.Tensor, *, want_
     Returns (logprob, [lse], [entropy], workspace) with the optional items present when asked for.
     """
     L = lib()
+    _check_device(H)
     dt = _dtype_code(H)
     T, d = H.shape
     V = W.shape[0]
@@ -177,6 +197,7 @@ def logprob_fwd(H: torch.Tensor, W: torch.Tensor, tokens: torch.Tensor, *, want_
 def sample_tokens(H: torch.Tensor, W: torch.Tensor, temperature: float, seed: int, *, want_scores: bool = False,
                   workspace: Optional[torch.Tensor] = None):
     """oapl_sample_tokens: one Gumbel-max draw per row from softmax(H W^T / temperature)."""
+    _check_device(H)
     dt = _dtype_code(H)
     T, d = H.shape
     V = W.shape[0]
@@ -209,10 +230,16 @@ class LossResult(NamedTuple):
 
 def loss_fwd_bwd(H, W, tokens, logq, seq_offsets, rewards, group_ids, n_groups: int, beta: float, *,
                  beta_value: Optional[float] = None, loss_scale: float = 1.0, backward: bool = True,
+                 two_pass: bool = False, max_panel_rows: Optional[int] = None,
                  workspace: Optional[torch.Tensor] = None, dH: Optional[torch.Tensor] = None,
                  dW: Optional[torch.Tensor] = None) -> LossResult:
-    """oapl_loss_fwd_bwd (or the two-beta entry point when beta_value is given)."""
+    """oapl_loss_fwd_bwd (or the two-beta entry point when beta_value or two_pass is given).
+
+    max_panel_rows only sizes the workspace this wrapper allocates when none is passed; the
+    library derives the panel from the bytes it is handed.
+    """
     L = lib()
+    _check_device(H)
     dt = _dtype_code(H)
     T, d = H.shape
     V = W.shape[0]
@@ -221,7 +248,7 @@ def loss_fwd_bwd(H, W, tokens, logq, seq_offsets, rewards, group_ids, n_groups: 
             or group_ids.shape != (n_seq,):
         raise ValueError("shape mismatch between the inputs")
     dev = H.device
-    nbytes = workspace_bytes(T, d, V, n_seq, n_groups, dt, backward)
+    nbytes = workspace_bytes(T, d, V, n_seq, n_groups, dt, backward, max_panel_rows)
     if nbytes == 0:
         raise OaplError(2, "oapl_workspace_bytes")
     ws = _workspace(nbytes, dev, workspace)
@@ -232,6 +259,8 @@ def loss_fwd_bwd(H, W, tokens, logq, seq_offsets, rewards, group_ids, n_groups: 
     if backward:
         dH = torch.empty_like(H) if dH is None else dH
         dW = torch.empty((V, d), dtype=torch.float32, device=dev) if dW is None else dW
+        if dH.shape != H.shape or dW.shape != (V, d):
+            raise ValueError("dH / dW have the wrong shape")
     else:
         dH = dW = None
     head = [_dev(H, H.dtype, "H", dev), _dev(W, H.dtype, "W", dev), _dev(tokens, torch.int32, "tokens", dev),
@@ -241,11 +270,12 @@ def loss_fwd_bwd(H, W, tokens, logq, seq_offsets, rewards, group_ids, n_groups: 
     tail = [loss.data_ptr(), logprob.data_ptr(), seq_lr.data_ptr(), vstar.data_ptr(),
             _dev(dH, H.dtype, "dH", dev), _dev(dW, torch.float32, "dW", dev), ws.data_ptr(), ws.numel(),
             _stream(dev)]
-    if beta_value is None:
+    if beta_value is None and not two_pass:
         rc = L.oapl_loss_fwd_bwd(*head, float(beta), float(loss_scale), *tail)
         where = "oapl_loss_fwd_bwd"
     else:
-        rc = L.oapl_loss_fwd_bwd_two_beta(*head, float(beta_value), float(beta), float(loss_scale), *tail)
+        rc = L.oapl_loss_fwd_bwd_two_beta(*head, float(beta if beta_value is None else beta_value), float(beta),
+                                          float(loss_scale), OAPL_FLAG_TWO_PASS if two_pass else 0, *tail)
         where = "oapl_loss_fwd_bwd_two_beta"
     if rc != 0:
         raise OaplError(rc, where)
@@ -263,9 +293,11 @@ class GrpoResult(NamedTuple):
 
 def grpo_loss_fwd_bwd(H, W, tokens, logq, logp_old, seq_offsets, rewards, group_ids, n_groups: int, *,
                       clip_eps: float = 0.2, adv_eps: float = 1e-6, loss_scale: float = 1.0, backward: bool = True,
+                      two_pass: bool = False, max_panel_rows: Optional[int] = None,
                       workspace: Optional[torch.Tensor] = None, dH: Optional[torch.Tensor] = None,
                       dW: Optional[torch.Tensor] = None) -> GrpoResult:
     """oapl_grpo_loss_fwd_bwd: the paper's GRPO + token-level importance sampling baseline."""
+    _check_device(H)
     dt = _dtype_code(H)
     T, d = H.shape
     V = W.shape[0]
@@ -274,7 +306,7 @@ def grpo_loss_fwd_bwd(H, W, tokens, logq, logp_old, seq_offsets, rewards, group_
             or seq_offsets.shape != (n_seq + 1,) or group_ids.shape != (n_seq,):
         raise ValueError("shape mismatch between the inputs")
     dev = H.device
-    nbytes = workspace_bytes(T, d, V, n_seq, n_groups, dt, backward)
+    nbytes = workspace_bytes(T, d, V, n_seq, n_groups, dt, backward, max_panel_rows)
     if nbytes == 0:
         raise OaplError(2, "oapl_workspace_bytes")
     ws = _workspace(nbytes, dev, workspace)
@@ -293,7 +325,8 @@ def grpo_loss_fwd_bwd(H, W, tokens, logq, logp_old, seq_offsets, rewards, group_
         _dev(logq, torch.float32, "logq", dev), _dev(logp_old, torch.float32, "logp_old", dev),
         _dev(seq_offsets, torch.int64, "seq_offsets", dev), _dev(rewards, torch.float32, "rewards", dev),
         _dev(group_ids, torch.int32, "group_ids", dev), T, d, V, n_seq, n_groups, dt, float(clip_eps), float(adv_eps),
-        float(loss_scale), loss.data_ptr(), logprob.data_ptr(), adv.data_ptr(), _dev(dH, H.dtype, "dH", dev),
+        float(loss_scale), OAPL_FLAG_TWO_PASS if two_pass else 0, loss.data_ptr(), logprob.data_ptr(), adv.data_ptr(),
+        _dev(dH, H.dtype, "dH", dev),
         _dev(dW, torch.float32, "dW", dev), ws.data_ptr(), ws.numel(), _stream(dev))
     if rc != 0:
         raise OaplError(rc, "oapl_grpo_loss_fwd_bwd")

@@ -56,7 +56,37 @@ def test_workspace_bytes_host_logic():
     assert wb(256, 64, (1 << 21) + 1, 8, 2, 0, False) == 0 and wb(256, (1 << 21) + 8, 1024, 8, 2, 0, False) == 0
     assert wb(65535 * 256 + 1, 64, 1024, 8, 2, oapl.OAPL_BF16, False) == 0
     assert wb(256, 60, 1024, 8, 2, oapl.OAPL_BF16, False) == 0     # bf16 rows must be 16-byte multiples
+    assert wb(65535 * 64 + 1, 64, 1024, 8, 2, oapl.OAPL_F32, False) == 0    # fp32 token tiles index gridDim.y
+    assert wb(65535 * 64, 64, 1024, 8, 2, oapl.OAPL_F32, False) > 0
+    assert wb(256, 64, 1024, 1 << 20, 1 << 13, 0, False) == 0      # n_seq * n_groups above 2^32
+    assert wb(256, 64, 1024, 1 << 20, 1 << 12, 0, False) > 0
     assert wb(0, 64, 1024, 0, 1, oapl.OAPL_BF16, True) > 0          # an empty batch is legal
+
+
+def test_workspace_is_the_memory_budget():
+    """oapl_workspace_bytes_for_panel: smaller panels need less workspace, the plan reports its panel."""
+    wbp = oapl.workspace_bytes_for_panel
+    args = (140897, 4096, 151936, 64, 8, oapl.OAPL_BF16, True)
+    full = oapl.workspace_bytes(*args)
+    assert wbp(*args, 0) == (full, wbp(*args, 61440)[1]) and wbp(*args, 1 << 40)[0] == full
+    prev = None
+    for cap in (384, 1000, 6144, 12288, 24576, 61440):
+        nbytes, rows = wbp(*args, cap)
+        assert nbytes > 0 and rows % 384 == 0 and 384 <= rows <= max(cap, 384)
+        assert prev is None or nbytes >= prev
+        prev = nbytes
+    # two panel pairs (tokens x V and V x tokens, bf16) dominate: 4 * rows * V * 2 bytes
+    nbytes, rows = wbp(*args, 12288)
+    assert rows == 12288 and 4 * rows * 151936 * 2 < nbytes < 4 * rows * 151936 * 2 + (5 << 30)
+    assert nbytes < 20 << 30
+    # one panel is enough when the batch fits it
+    assert wbp(6000, 4096, 151936, 8, 1, oapl.OAPL_BF16, True, 6144)[1] == 6144
+    # fp32: the panel is the logit-gradient block [rows, V]
+    a, ra = wbp(5000, 64, 1024, 8, 2, oapl.OAPL_F32, True, 0)
+    b, rb = wbp(5000, 64, 1024, 8, 2, oapl.OAPL_F32, True, 512)
+    assert (ra, rb) == (4096, 512) and a - b == (4096 - 512) * 1024 * 4
+    # invalid sizes answer 0 like oapl_workspace_bytes
+    assert wbp(-1, 64, 1024, 8, 2, 0, True, 512) == (0, 0)
 
 
 def test_host_side_errors_return_before_any_launch():
@@ -78,15 +108,18 @@ def test_host_side_errors_return_before_any_launch():
     assert loss(beta=float("inf")) == 6 and loss(scale=float("inf")) == 6
     assert loss(dH=None) == 1 and loss(dW=None) == 1          # gradients come as a pair
     assert loss(dtype=9) == 3 and loss(n_groups=0) == 2 and loss(ws_bytes=64) == 7
-    assert L.oapl_loss_fwd_bwd_two_beta(one, one, one, one, one, one, one, 4, 8, 8, 2, 1, 0, 1.0, 0.0, 1.0,
-                                        one, None, None, None, one, one, one, 1 << 24, None) == 6
+    def two_beta(beta_loss=1.0, flags=0):
+        return L.oapl_loss_fwd_bwd_two_beta(one, one, one, one, one, one, one, 4, 8, 8, 2, 1, 0, 1.0, beta_loss, 1.0,
+                                            flags, one, None, None, None, one, one, one, 1 << 24, None)
+    assert two_beta(beta_loss=0.0) == 6
+    assert two_beta(flags=2) == 2 and two_beta(flags=0x80000000) == 2       # unknown option bits
     # GRPO baseline: clip in [0, 1), adv_eps >= 0, finite scale; gradients as a pair; logp_old required
-    def grpo(clip=0.2, eps=1e-6, scale=1.0, old=one, dH=one, dW=one, dtype=0):
+    def grpo(clip=0.2, eps=1e-6, scale=1.0, old=one, dH=one, dW=one, dtype=0, flags=0):
         return L.oapl_grpo_loss_fwd_bwd(one, one, one, one, old, one, one, one, 4, 8, 8, 2, 1, dtype, clip, eps,
-                                        scale, one, None, None, dH, dW, one, 1 << 24, None)
+                                        scale, flags, one, None, None, dH, dW, one, 1 << 24, None)
     assert grpo(clip=1.0) == 6 and grpo(clip=-0.1) == 6 and grpo(clip=float("nan")) == 6
     assert grpo(eps=-1.0) == 6 and grpo(eps=float("inf")) == 6 and grpo(scale=float("nan")) == 6
-    assert grpo(old=None) == 1 and grpo(dH=None) == 1 and grpo(dtype=5) == 3
+    assert grpo(old=None) == 1 and grpo(dH=None) == 1 and grpo(dtype=5) == 3 and grpo(flags=4) == 2
     # sampling: temperature must be positive and finite
     assert L.oapl_sample_tokens(one, one, 4, 8, 8, 0, 0.0, 1, one, None, one, 1 << 20, None) == 6
     assert L.oapl_sample_tokens(one, one, 4, 8, 8, 0, float("nan"), 1, one, None, one, 1 << 20, None) == 6

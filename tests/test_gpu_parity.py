@@ -29,10 +29,19 @@ def schedule(request):
     """Every test of this file runs under both schedules of the bf16 loss entry points: the single
     sweep over the logits (default) and the two-pass schedule it falls back to."""
     _MODE[0] = request.param
-    oapl.single_sweep_enable(request.param == "single_sweep")
     yield request.param
-    oapl.single_sweep_enable(True)
     _MODE[0] = "single_sweep"
+
+
+def _loss(*a, **kw):
+    """oapl.loss_fwd_bwd under the schedule the fixture selected (a per-call flag of the C ABI)."""
+    kw.setdefault("two_pass", _MODE[0] == "two_pass")
+    return oapl.loss_fwd_bwd(*a, **kw)
+
+
+def _grpo(*a, **kw):
+    kw.setdefault("two_pass", _MODE[0] == "two_pass")
+    return oapl.grpo_loss_fwd_bwd(*a, **kw)
 
 
 def _sweep_tried(b, res):
@@ -41,7 +50,7 @@ def _sweep_tried(b, res):
 
 
 def _run(b, **kw):
-    res = oapl.loss_fwd_bwd(b.H, b.W, b.tokens, b.logq, b.seq_offsets, b.rewards, b.group_ids, b.n_groups,
+    res = _loss(b.H, b.W, b.tokens, b.logq, b.seq_offsets, b.rewards, b.group_ids, b.n_groups,
                             kw.pop("beta", b.beta), **kw)
     torch.cuda.synchronize()
     return res
@@ -156,6 +165,37 @@ def test_bf16_rollout_longer_than_a_panel_takes_two_passes():
     res = _run(b)
     ref = oracle_full(b)
     _check(b, res, ref, lp_tol=2e-2, rel_tol=1e-3, g_rtol=2e-2, g_atol_frac=6e-3, fallback=True)
+
+
+@pytest.mark.parametrize("cap,lens,fallback", [
+    (384, [300, 380, 0, 200, 350, 90, 384, 1], False),    # 5 one-tile panels, rollouts straddle every boundary
+    (768, [700, 33, 768, 500, 2, 640], False),            # 4 two-tile panels
+    (384, [500, 300, 700, 200], True),                    # rollouts longer than the panel: two passes, same results
+])
+def test_bf16_workspace_budget_sets_the_panel(cap, lens, fallback):
+    """The workspace is the memory budget: handed one sized for panels of `cap` rows, the call works
+    in panels of that size (several of them here, with rollouts straddling the boundaries) and gives
+    the same results; a workspace one byte short of the smallest plan is refused."""
+    b = _custom_batch("bf16", d=128, V=1300, lens=lens, n_groups=2, seed=31, beta=0.8, noise=0.1)
+    nbytes, rows = oapl.workspace_bytes_for_panel(b.T, 128, 1300, len(lens), 2, oapl.OAPL_BF16, True, cap)
+    assert rows == cap and nbytes < oapl.workspace_bytes(b.T, 128, 1300, len(lens), 2, oapl.OAPL_BF16, True)
+    ws = torch.empty(nbytes, dtype=torch.uint8, device=DEV)
+    res = _run(b, workspace=ws)
+    ref = oracle_full(b)
+    _check(b, res, ref, lp_tol=2e-2, rel_tol=1e-3, g_rtol=2e-2, g_atol_frac=6e-3, fallback=fallback)
+    least = oapl.workspace_bytes_for_panel(b.T, 128, 1300, len(lens), 2, oapl.OAPL_BF16, True, 1)[0]
+    with pytest.raises(oapl.OaplError) as e:
+        _run(b, workspace=torch.empty(least - 256, dtype=torch.uint8, device=DEV))
+    assert e.value.status == 7
+
+
+def test_f32_workspace_budget_sets_the_panel():
+    lens = [0, 1, 37, 64, 0, 129, 5, 64]
+    b = _custom_batch("f32", d=72, V=1000, lens=lens, n_groups=3, seed=1, beta=0.7)
+    nbytes, rows = oapl.workspace_bytes_for_panel(b.T, 72, 1000, len(lens), 3, oapl.OAPL_F32, True, 100)
+    assert rows == 100
+    res = _run(b, workspace=torch.empty(nbytes, dtype=torch.uint8, device=DEV))
+    _check(b, res, oracle_full(b), lp_tol=1e-5, rel_tol=1e-5, g_rtol=1e-4, g_atol_frac=3e-6)
 
 
 def test_bf16_logit_outside_the_sweep_range_takes_two_passes():
@@ -386,18 +426,18 @@ def test_device_side_errors_are_reported_not_faulted():
     # offsets that do not end at T
     off = b.seq_offsets.clone()
     off[-1] = 63
-    res = oapl.loss_fwd_bwd(b.H, b.W, b.tokens, b.logq, off, b.rewards, b.group_ids, 2, 1.0)
+    res = _loss(b.H, b.W, b.tokens, b.logq, off, b.rewards, b.group_ids, 2, 1.0)
     assert oapl.read_device_status(res.workspace) == 4 and torch.isnan(res.loss.cpu()).all()
     # decreasing offsets (would index backwards if trusted)
     off = torch.tensor([0, 70, 64], dtype=torch.int64, device=DEV)
-    res = oapl.loss_fwd_bwd(b.H, b.W, b.tokens, b.logq, off, b.rewards, b.group_ids, 2, 1.0)
+    res = _loss(b.H, b.W, b.tokens, b.logq, off, b.rewards, b.group_ids, 2, 1.0)
     assert oapl.read_device_status(res.workspace) == 4 and torch.isnan(res.loss.cpu()).all()
     # group id out of range, then an empty group
     gid = torch.tensor([0, 2], dtype=torch.int32, device=DEV)
-    res = oapl.loss_fwd_bwd(b.H, b.W, b.tokens, b.logq, b.seq_offsets, b.rewards, gid, 2, 1.0)
+    res = _loss(b.H, b.W, b.tokens, b.logq, b.seq_offsets, b.rewards, gid, 2, 1.0)
     assert oapl.read_device_status(res.workspace) == 5 and torch.isnan(res.loss.cpu()).all()
     gid = torch.tensor([1, 1], dtype=torch.int32, device=DEV)
-    res = oapl.loss_fwd_bwd(b.H, b.W, b.tokens, b.logq, b.seq_offsets, b.rewards, gid, 2, 1.0)
+    res = _loss(b.H, b.W, b.tokens, b.logq, b.seq_offsets, b.rewards, gid, 2, 1.0)
     assert oapl.read_device_status(res.workspace) == 5 and torch.isnan(res.loss.cpu()).all()
 
 
@@ -410,7 +450,7 @@ def test_empty_batch_and_forward_only():
     off = torch.zeros(3, dtype=torch.int64, device=dev)
     rewards = torch.tensor([1.0, 0.0], device=dev)
     gid = torch.zeros(2, dtype=torch.int32, device=dev)
-    res = oapl.loss_fwd_bwd(H, W, tok, logq, off, rewards, gid, 1, 1.0)
+    res = _loss(H, W, tok, logq, off, rewards, gid, 1, 1.0)
     torch.cuda.synchronize()
     # no tokens: every log-ratio is 0, the loss is the sum of squared advantages and dW is zero
     v = np.log(0.5 * (np.e + 1.0))
@@ -495,11 +535,11 @@ def test_grpo_baseline_f32():
     b = _custom_batch("f32", d=72, V=1000, lens=lens, n_groups=3, seed=21, beta=1.0)
     b.rewards = torch.tensor([1, 0, 0, 1, 1, 0, 1, 1, 0], dtype=torch.float32, device=DEV)
     logq, logp_old = _grpo_inputs(b, 21)
-    res = oapl.grpo_loss_fwd_bwd(b.H, b.W, b.tokens, logq, logp_old, b.seq_offsets, b.rewards, b.group_ids, 3,
+    res = _grpo(b.H, b.W, b.tokens, logq, logp_old, b.seq_offsets, b.rewards, b.group_ids, 3,
                                  clip_eps=0.2, adv_eps=1e-6, loss_scale=0.5)
     torch.cuda.synchronize()
     _grpo_check(b, logq, logp_old, res, 1e-5, 1e-5, 1e-4, 3e-6, clip_eps=0.2, adv_eps=1e-6, loss_scale=0.5)
-    fwd = oapl.grpo_loss_fwd_bwd(b.H, b.W, b.tokens, logq, logp_old, b.seq_offsets, b.rewards, b.group_ids, 3,
+    fwd = _grpo(b.H, b.W, b.tokens, logq, logp_old, b.seq_offsets, b.rewards, b.group_ids, 3,
                                  clip_eps=0.2, adv_eps=1e-6, loss_scale=0.5, backward=False)
     assert fwd.dH is None and torch.equal(fwd.loss, res.loss) and torch.equal(fwd.logprob, res.logprob)
 
@@ -513,7 +553,7 @@ def test_grpo_baseline_bf16(d, V, lens, seed):
     b.rewards = torch.tensor([1.0, 0.0] * (len(lens) // 2), device=DEV)
     b.group_ids = torch.tensor([0, 0, 1, 1] * (len(lens) // 4), dtype=torch.int32, device=DEV)
     logq, logp_old = _grpo_inputs(b, seed)
-    res = oapl.grpo_loss_fwd_bwd(b.H, b.W, b.tokens, logq, logp_old, b.seq_offsets, b.rewards, b.group_ids, 2)
+    res = _grpo(b.H, b.W, b.tokens, logq, logp_old, b.seq_offsets, b.rewards, b.group_ids, 2)
     torch.cuda.synchronize()
     _grpo_check(b, logq, logp_old, res, 2e-2, 1e-3, 2e-2, 6e-3)
 
@@ -524,20 +564,20 @@ def test_grpo_degenerate_groups_and_errors():
     logq, logp_old = _grpo_inputs(b, 24)
     # every rollout of a prompt with the same reward: zero advantage, zero loss, zero gradient
     same = torch.tensor([1.0, 1.0, 0.0, 0.0], device=DEV)
-    res = oapl.grpo_loss_fwd_bwd(b.H, b.W, b.tokens, logq, logp_old, b.seq_offsets, same, b.group_ids, 2)
+    res = _grpo(b.H, b.W, b.tokens, logq, logp_old, b.seq_offsets, same, b.group_ids, 2)
     assert oapl.read_device_status(res.workspace) == 0
     assert res.loss.item() == 0.0 and float(res.advantages.abs().max()) == 0.0
     assert float(res.dW.abs().max()) == 0.0 and float(res.dH.float().abs().max()) == 0.0
     # bad offsets and group ids: status and NaN loss, no fault
     off = b.seq_offsets.clone()
     off[-1] = 79
-    res = oapl.grpo_loss_fwd_bwd(b.H, b.W, b.tokens, logq, logp_old, off, b.rewards, b.group_ids, 2)
+    res = _grpo(b.H, b.W, b.tokens, logq, logp_old, off, b.rewards, b.group_ids, 2)
     assert oapl.read_device_status(res.workspace) == 4 and torch.isnan(res.loss.cpu()).all()
     gid = torch.tensor([0, 0, 0, 5], dtype=torch.int32, device=DEV)
-    res = oapl.grpo_loss_fwd_bwd(b.H, b.W, b.tokens, logq, logp_old, b.seq_offsets, b.rewards, gid, 2)
+    res = _grpo(b.H, b.W, b.tokens, logq, logp_old, b.seq_offsets, b.rewards, gid, 2)
     assert oapl.read_device_status(res.workspace) == 5 and torch.isnan(res.loss.cpu()).all()
     with pytest.raises(oapl.OaplError):
-        oapl.grpo_loss_fwd_bwd(b.H, b.W, b.tokens, logq, logp_old, b.seq_offsets, b.rewards, b.group_ids, 2,
+        _grpo(b.H, b.W, b.tokens, logq, logp_old, b.seq_offsets, b.rewards, b.group_ids, 2,
                                clip_eps=1.5)
 
 
@@ -552,7 +592,7 @@ def test_loss_call_replays_from_a_hip_graph():
     logq = b.logq.clone()
 
     def call():
-        return oapl.loss_fwd_bwd(b.H, b.W, b.tokens, logq, b.seq_offsets, b.rewards, b.group_ids, 2, b.beta,
+        return _loss(b.H, b.W, b.tokens, logq, b.seq_offsets, b.rewards, b.group_ids, 2, b.beta,
                                  workspace=ws, dH=dH, dW=dW)
     call()                                   # first call outside the capture: one-time kernel attributes
     torch.cuda.synchronize()
@@ -585,7 +625,7 @@ def test_calls_on_two_streams_with_own_workspaces_do_not_interfere():
     got = []
     for b, st in zip((ba, bb), streams):
         with torch.cuda.stream(st):
-            got.append(oapl.loss_fwd_bwd(b.H, b.W, b.tokens, b.logq, b.seq_offsets, b.rewards, b.group_ids,
+            got.append(_loss(b.H, b.W, b.tokens, b.logq, b.seq_offsets, b.rewards, b.group_ids,
                                          b.n_groups, b.beta))
     torch.cuda.synchronize()
     for g, w in zip(got, want):
