@@ -60,7 +60,8 @@ typedef enum {
   OAPL_ERR_BETA = 6,        /* beta (or loss_scale) not finite or beta <= 0 */
   OAPL_ERR_WORKSPACE = 7,   /* workspace NULL, misaligned or too small */
   OAPL_ERR_HIP = 8,         /* a HIP launch or runtime call failed */
-  OAPL_ERR_TOKEN_RANGE = 9  /* device: sampled token outside [0, V) */
+  OAPL_ERR_TOKEN_RANGE = 9, /* device: sampled token outside [0, V) */
+  OAPL_ERR_SCRATCH_LIMIT = 10 /* oapl_loss_fwd_bwd_noalloc: the sizes need more than the static scratch */
 } oapl_status;
 
 typedef enum {
@@ -235,6 +236,34 @@ int32_t oapl_loss_fwd_bwd_two_beta(const void* H, const void* W, const int32_t* 
                                    uint32_t flags, float* loss_out, float* logprob_out, float* seq_logratio_out,
                                    float* vstar_out, void* dH, float* dW,
                                    void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * oapl_loss_fwd_bwd for callers that cannot allocate device memory at all (code
+ * under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc) and so cannot bring a workspace either: the same computation with
+ * the same kernels, its scratch taken from an array the library itself holds in
+ * device memory (64 MiB on every GPU the library runs on, from the first call
+ * on that GPU until the process ends).  The call allocates and frees nothing.
+ *   - Sizes whose plan (with the largest backward panel that fits) needs more
+ *     than 64 MiB return OAPL_ERR_SCRATCH_LIMIT before anything is launched;
+ *     small heads and batches fit (d = 256, V = 1544, T = 1000 needs about 12 MiB).
+ *   - All calls on one GPU share that GPU's array, which keeps the last call's
+ *     contents; the call clears what it needs cleared.  Calls that overlap on
+ *     one GPU (different streams or host threads) race: serialise them.
+ *   - The first call on a GPU resolves the array's device address (a HIP
+ *     runtime call that may load the code object): make that call outside any
+ *     graph capture.
+ *   - The device-side status record lives in the library's scratch and cannot
+ *     be read back; errors in device data show as NaN in the affected outputs.
+ * Arguments as for oapl_loss_fwd_bwd, without workspace and workspace_bytes.
+ */
+int32_t oapl_loss_fwd_bwd_noalloc(const void* H, const void* W, const int32_t* tokens,
+                                  const float* logq, const int64_t* seq_offsets,
+                                  const float* rewards, const int32_t* group_ids,
+                                  int64_t T, int32_t d, int32_t V, int32_t n_seq, int32_t n_groups,
+                                  int32_t dtype, float beta, float loss_scale,
+                                  float* loss_out, float* logprob_out, float* seq_logratio_out,
+                                  float* vstar_out, void* dH, float* dW, void* stream);
 
 /*
  * The paper's baseline on the same fused head: GRPO with token-level importance

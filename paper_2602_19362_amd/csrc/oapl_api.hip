@@ -526,7 +526,8 @@ static int loss_impl(const void* H, const void* W, const int32_t* tokens, const 
                      const int64_t* seq_offsets, const float* rewards, const int32_t* group_ids, int64_t T, int32_t d,
                      int32_t V, int32_t n_seq, int32_t n_groups, int32_t dtype, float beta_value, float beta_loss,
                      float loss_scale, uint32_t flags, float* loss_out, float* logprob_out, float* seq_logratio_out,
-                     float* vstar_out, void* dH, float* dW, void* workspace, size_t workspace_bytes, void* stream) {
+                     float* vstar_out, void* dH, float* dW, void* workspace, size_t workspace_bytes, void* stream,
+                     bool checks_only = false) {
   if (dtype != OAPL_F32 && dtype != OAPL_BF16) return OAPL_ERR_DTYPE;
   if (flags & ~(uint32_t)OAPL_FLAG_TWO_PASS) return OAPL_ERR_SHAPE;
   const bool bwd = (dH != nullptr) || (dW != nullptr);
@@ -540,6 +541,7 @@ static int loss_impl(const void* H, const void* W, const int32_t* tokens, const 
       !isfinite(loss_scale))
     return OAPL_ERR_BETA;
   if (int rc = fit_plan(p, T, d, V, n_seq, n_groups, dtype, bwd, workspace, workspace_bytes)) return rc;
+  if (checks_only) return OAPL_OK;
 
   hipStream_t st = (hipStream_t)stream;
   char* ws = (char*)workspace;
@@ -656,6 +658,30 @@ static int grpo_impl(const void* H, const void* W, const int32_t* tokens, const 
   return backward_grads(p, H, W, tokens, dH, dW, ws, st, slow, sweep);
 }
 
+// Scratch of the entry point that allocates nothing: every GPU the library runs on holds its own
+// copy of this array, at its own address, until the process ends.
+constexpr size_t kStaticScratchBytes = (size_t)64 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+// Device address of `scratch` on the current device (the array's name is only a host-side stand-in
+// for it): resolved once per device, with that device current, and kept.
+constexpr int kMaxDevices = 64;
+static void* g_scratch_ptr[kMaxDevices];
+static std::mutex g_scratch_mu;
+
+static int static_scratch(void** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return OAPL_ERR_HIP;
+  std::lock_guard<std::mutex> g(g_scratch_mu);
+  if (g_scratch_ptr[dev] == nullptr) {
+    void* ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || ptr == nullptr) return OAPL_ERR_HIP;
+    g_scratch_ptr[dev] = ptr;
+  }
+  *out = g_scratch_ptr[dev];
+  return OAPL_OK;
+}
+
 }  // namespace oapl
 
 using namespace oapl;
@@ -674,6 +700,7 @@ const char* oapl_status_string(int32_t status) {
     case OAPL_ERR_WORKSPACE: return "workspace NULL, misaligned or too small";
     case OAPL_ERR_HIP: return "HIP launch or runtime call failed";
     case OAPL_ERR_TOKEN_RANGE: return "sampled token outside [0, V)";
+    case OAPL_ERR_SCRATCH_LIMIT: return "sizes need more than the library's 64 MiB static scratch";
     default: return "unknown status";
   }
 }
@@ -774,6 +801,24 @@ int32_t oapl_loss_fwd_bwd_two_beta(const void* H, const void* W, const int32_t* 
   return loss_impl(H, W, tokens, logq, seq_offsets, rewards, group_ids, T, d, V, n_seq, n_groups, dtype, beta_value,
                    beta_loss, loss_scale, flags, loss_out, logprob_out, seq_logratio_out, vstar_out, dH, dW, workspace,
                    workspace_bytes, stream);
+}
+
+int32_t oapl_loss_fwd_bwd_noalloc(const void* H, const void* W, const int32_t* tokens, const float* logq,
+                                  const int64_t* seq_offsets, const float* rewards, const int32_t* group_ids,
+                                  int64_t T, int32_t d, int32_t V, int32_t n_seq, int32_t n_groups, int32_t dtype,
+                                  float beta, float loss_scale, float* loss_out, float* logprob_out,
+                                  float* seq_logratio_out, float* vstar_out, void* dH, float* dW, void* stream) {
+  // every host-side check first, against an aligned stand-in of the scratch's size; nothing is launched
+  int rc = loss_impl(H, W, tokens, logq, seq_offsets, rewards, group_ids, T, d, V, n_seq, n_groups, dtype, beta, beta,
+                     loss_scale, 0u, loss_out, logprob_out, seq_logratio_out, vstar_out, dH, dW, (void*)(uintptr_t)256,
+                     kStaticScratchBytes, stream, true);
+  if (rc == OAPL_ERR_WORKSPACE) return OAPL_ERR_SCRATCH_LIMIT;
+  if (rc != OAPL_OK) return rc;
+  void* ws = nullptr;
+  if ((rc = static_scratch(&ws)) != OAPL_OK) return rc;
+  return loss_impl(H, W, tokens, logq, seq_offsets, rewards, group_ids, T, d, V, n_seq, n_groups, dtype, beta, beta,
+                   loss_scale, 0u, loss_out, logprob_out, seq_logratio_out, vstar_out, dH, dW, ws, kStaticScratchBytes,
+                   stream);
 }
 
 int32_t oapl_grpo_loss_fwd_bwd(const void* H, const void* W, const int32_t* tokens, const float* logq,

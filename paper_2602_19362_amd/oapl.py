@@ -23,6 +23,7 @@ OAPL_FLAG_TWO_PASS = 1
 STATUS_NAMES = {
     0: "OAPL_OK", 1: "OAPL_ERR_NULL", 2: "OAPL_ERR_SHAPE", 3: "OAPL_ERR_DTYPE", 4: "OAPL_ERR_OFFSETS",
     5: "OAPL_ERR_GROUP", 6: "OAPL_ERR_BETA", 7: "OAPL_ERR_WORKSPACE", 8: "OAPL_ERR_HIP", 9: "OAPL_ERR_TOKEN_RANGE",
+    10: "OAPL_ERR_SCRATCH_LIMIT",
 }
 
 # Every symbol include/oapl.h declares, with its ctypes signature.
@@ -43,6 +44,8 @@ _SIGNATURES = {
                           [_c.c_void_p] * 7 + [_c.c_size_t, _c.c_void_p]),
     "oapl_loss_fwd_bwd_two_beta": (_c.c_int32, [_c.c_void_p] * 7 + [_c.c_int64] + [_c.c_int32] * 5 + [_c.c_float] * 3 +
                                    [_c.c_uint32] + [_c.c_void_p] * 7 + [_c.c_size_t, _c.c_void_p]),
+    "oapl_loss_fwd_bwd_noalloc": (_c.c_int32, [_c.c_void_p] * 7 + [_c.c_int64] + [_c.c_int32] * 5 + [_c.c_float] * 2 +
+                                  [_c.c_void_p] * 7),
     "oapl_grpo_loss_fwd_bwd": (_c.c_int32, [_c.c_void_p] * 8 + [_c.c_int64] + [_c.c_int32] * 5 + [_c.c_float] * 3 +
                                [_c.c_uint32] + [_c.c_void_p] * 6 + [_c.c_size_t, _c.c_void_p]),
     "oapl_segmented_sum_f32": (_c.c_int32, [_c.c_void_p, _c.c_void_p, _c.c_int32, _c.c_void_p, _c.c_void_p]),
@@ -280,6 +283,34 @@ def loss_fwd_bwd(H, W, tokens, logq, seq_offsets, rewards, group_ids, n_groups: 
     if rc != 0:
         raise OaplError(rc, where)
     return LossResult(loss, logprob, seq_lr, vstar, dH, dW, ws)
+
+
+def loss_fwd_bwd_noalloc(H, W, tokens, logq, seq_offsets, rewards, group_ids, n_groups: int, beta: float,
+                         loss: torch.Tensor, logprob: torch.Tensor, seq_logratio: torch.Tensor, vstar: torch.Tensor,
+                         dH: Optional[torch.Tensor], dW: Optional[torch.Tensor], *, loss_scale: float = 1.0) -> None:
+    """oapl_loss_fwd_bwd_noalloc: every output is passed in; neither this wrapper nor the library allocates."""
+    _check_device(H)
+    dt = _dtype_code(H)
+    T, d = H.shape
+    V = W.shape[0]
+    n_seq = rewards.shape[0]
+    if W.shape[1] != d or tokens.shape != (T,) or logq.shape != (T,) or seq_offsets.shape != (n_seq + 1,) \
+            or group_ids.shape != (n_seq,) or loss.shape != (1,) or logprob.shape != (T,) \
+            or seq_logratio.shape != (n_seq,) or vstar.shape != (n_groups,):
+        raise ValueError("shape mismatch between the arguments")
+    if (dH is None) != (dW is None) or (dH is not None and (dH.shape != H.shape or dW.shape != (V, d))):
+        raise ValueError("dH / dW must come as a pair of the right shapes")
+    dev = H.device
+    rc = lib().oapl_loss_fwd_bwd_noalloc(
+        _dev(H, H.dtype, "H", dev), _dev(W, H.dtype, "W", dev), _dev(tokens, torch.int32, "tokens", dev),
+        _dev(logq, torch.float32, "logq", dev), _dev(seq_offsets, torch.int64, "seq_offsets", dev),
+        _dev(rewards, torch.float32, "rewards", dev), _dev(group_ids, torch.int32, "group_ids", dev),
+        T, d, V, n_seq, n_groups, dt, float(beta), float(loss_scale),
+        _dev(loss, torch.float32, "loss", dev), _dev(logprob, torch.float32, "logprob", dev),
+        _dev(seq_logratio, torch.float32, "seq_logratio", dev), _dev(vstar, torch.float32, "vstar", dev),
+        _dev(dH, H.dtype, "dH", dev), _dev(dW, torch.float32, "dW", dev), _stream(dev))
+    if rc != 0:
+        raise OaplError(rc, "oapl_loss_fwd_bwd_noalloc")
 
 
 class GrpoResult(NamedTuple):

@@ -29,8 +29,8 @@ def test_library_exports_every_declared_symbol():
 def test_status_strings():
     L = oapl.lib()
     assert L.oapl_status_string(0) == b"ok"
-    seen = {L.oapl_status_string(i) for i in range(10)}
-    assert len(seen) == 10 and L.oapl_status_string(77) == b"unknown status"
+    seen = {L.oapl_status_string(i) for i in range(11)}
+    assert len(seen) == 11 and L.oapl_status_string(77) == b"unknown status"
 
 
 def test_workspace_bytes_host_logic():
@@ -113,6 +113,13 @@ def test_host_side_errors_return_before_any_launch():
                                             flags, one, None, None, None, one, one, one, 1 << 24, None)
     assert two_beta(beta_loss=0.0) == 6
     assert two_beta(flags=2) == 2 and two_beta(flags=0x80000000) == 2       # unknown option bits
+    # the entry point that allocates nothing: same checks, and sizes beyond its 64 MiB scratch are refused
+    def noalloc(beta=1.0, T=4, d=8, V=8, dtype=0, dW=one):
+        return L.oapl_loss_fwd_bwd_noalloc(one, one, one, one, one, one, one, T, d, V, 2, 1, dtype, beta, 1.0,
+                                           one, None, None, None, one, dW, None)
+    assert noalloc(beta=0.0) == 6 and noalloc(dtype=4) == 3 and noalloc(d=0) == 2 and noalloc(dW=None) == 1
+    assert noalloc(T=1000, d=4096, V=151936, dtype=1) == 10
+    assert L.oapl_status_string(10).startswith(b"sizes need more than")
     # GRPO baseline: clip in [0, 1), adv_eps >= 0, finite scale; gradients as a pair; logp_old required
     def grpo(clip=0.2, eps=1e-6, scale=1.0, old=one, dH=one, dW=one, dtype=0, flags=0):
         return L.oapl_grpo_loss_fwd_bwd(one, one, one, one, old, one, one, one, 4, 8, 8, 2, 1, dtype, clip, eps,

@@ -1,0 +1,69 @@
+"""oapl_loss_fwd_bwd_noalloc (the entry point for callers that cannot allocate: its scratch is an
+array the library holds on the device) against oapl_loss_fwd_bwd on the same inputs: two calls in a
+row on the shared scratch, the second with a smaller batch, plus the size limit."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2602_19362_amd import oapl, synth
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+
+
+def _batch(dtype, d, V, lens, seed):
+    cfg = synth.RolloutConfig(name="noalloc", dtype=dtype, d=d, V=V, n_prompts=2, n_rollouts=len(lens) // 2,
+                              length="fixed", len_fixed=1, logq_sigma=0.1, beta=0.7, seed_index=seed)
+    g = torch.Generator(device=DEV)
+    g.manual_seed(7000 + seed)
+    T = int(sum(lens))
+    dt = torch.float32 if dtype == "f32" else torch.bfloat16
+    H = torch.randn(T, d, generator=g, device=DEV).to(dt)
+    W = (torch.randn(V, d, generator=g, device=DEV) / d ** 0.5).to(dt)
+    tokens = torch.randint(0, V, (T,), generator=g, device=DEV).to(torch.int32)
+    logq = (synth.engine_logprobs(H, W, tokens) + 0.1 * torch.randn(T, generator=g, device=DEV)).contiguous()
+    off = torch.from_numpy(np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)).to(DEV)
+    rewards = (torch.rand(len(lens), generator=g, device=DEV) < 0.5).float()
+    gid = (torch.arange(len(lens), device=DEV) % 2).to(torch.int32)
+    return H, W, tokens, logq, off, rewards, gid
+
+
+def _both_ways(dtype, d, V, lens, seed):
+    H, W, tokens, logq, off, rewards, gid = _batch(dtype, d, V, lens, seed)
+    T, n = H.shape[0], len(lens)
+    ref = oapl.loss_fwd_bwd(H, W, tokens, logq, off, rewards, gid, 2, 0.7)
+    torch.cuda.synchronize()
+    assert oapl.read_device_status(ref.workspace) == 0
+    out = dict(loss=torch.full((1,), float("nan"), device=DEV), logprob=torch.full((T,), float("nan"), device=DEV),
+               seq_logratio=torch.full((n,), float("nan"), device=DEV), vstar=torch.full((2,), float("nan"), device=DEV),
+               dH=torch.full_like(H, float("nan")), dW=torch.full((V, d), float("nan"), device=DEV))
+    oapl.loss_fwd_bwd_noalloc(H, W, tokens, logq, off, rewards, gid, 2, 0.7, **out)
+    torch.cuda.synchronize()
+    # same kernels, same plan, fixed summation orders: the two entry points agree to the last bit
+    for name in ("loss", "logprob", "seq_logratio", "vstar", "dH", "dW"):
+        assert torch.equal(out[name], getattr(ref, name)), name
+    assert bool(torch.isfinite(out["dW"]).all()) and bool(torch.isfinite(out["dH"].float()).all())
+
+
+@pytest.mark.parametrize("dtype,d,V,first,second", [
+    ("bf16", 256, 1544, [300, 200, 77, 150, 0, 420], [100, 60]),     # single sweep; 3 token tiles, then 1
+    ("bf16", 128, 900, [30, 20], [5, 7]),                            # fewer than 64 tokens: two passes
+    ("f32", 64, 1024, [32] * 8, [9, 0, 3, 1]),
+])
+def test_noalloc_entry_point_matches_the_workspace_entry_point(dtype, d, V, first, second):
+    _both_ways(dtype, d, V, first, 1)
+    _both_ways(dtype, d, V, second, 2)       # smaller input on the scratch the first call left behind
+
+
+def test_noalloc_entry_point_refuses_sizes_beyond_its_scratch():
+    H, W, tokens, logq, off, rewards, gid = _batch("bf16", 64, 264, [40, 24], 3)
+    T = H.shape[0]
+    big_V = 1 << 20       # packed W alone (2^20 x 64 bf16 = 128 MiB) exceeds the 64 MiB scratch
+    Wbig = torch.zeros(big_V, 64, dtype=torch.bfloat16, device=DEV)
+    with pytest.raises(oapl.OaplError) as e:
+        oapl.loss_fwd_bwd_noalloc(H, Wbig, tokens, logq, off, rewards, gid, 2, 0.7,
+                                  loss=torch.empty(1, device=DEV), logprob=torch.empty(T, device=DEV),
+                                  seq_logratio=torch.empty(2, device=DEV), vstar=torch.empty(2, device=DEV),
+                                  dH=torch.empty_like(H), dW=torch.empty(big_V, 64, device=DEV))
+    assert e.value.status == 10
