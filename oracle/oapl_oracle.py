@@ -46,7 +46,8 @@ scipy's log_softmax and logsumexp, the beta -> 0 / beta -> infinity limits of
 Eq. 2, the all-equal-rewards closed form V* = r, the binary-reward closed form,
 the pi = pi_vllm closed form of Eq. 3, the constructed minimiser of Eq. 3
 (loss 0, gradient 0), central finite differences for every element of dH
-and dW, and for the entropy: ln V for uniform logits, 50-digit brute force,
+and dW (the row-wise forms grad_hidden_rows / grad_weight_rows: equality with
+those), and for the entropy: ln V for uniform logits, 50-digit brute force,
 scipy.stats.entropy, the bounds 0 <= H <= ln V and shift invariance.  No
 value the paper prints exists for this path (it prints no worked example), so
 full-size numbers are pinned by these properties only.
@@ -294,6 +295,27 @@ def grad_hidden_rows(H, W, tokens, coeff, rows, slab: int = 256) -> np.ndarray:
         p = np.exp(logp)
         out[a:a + r.size] = coeff[r, None] * (W64[tokens[r]] - p @ W64)
     return out
+
+
+def grad_weight_rows(H, W_rows, vocab_rows, tokens, coeff, lse) -> np.ndarray:
+    """dL/dW for the selected vocabulary rows, from the token rows given:
+
+        dW[v, :] = sum_t c_t * (1[v == y_t] - exp(z_{t,v} - lse_t)) * H[t, :],   z_{t,v} = W[v, :] . H[t, :]
+
+    (chain rule on Eq. 3, with the soft-max written through the log-partition lse_t of each token
+    row).  ``W_rows`` are the selected rows of W, ``vocab_rows`` their indices v.  The sum over t is
+    linear: a caller that cannot hold all token rows at once adds up the results of slabs.
+    """
+    H64 = _f64(H)
+    Wr = _f64(W_rows)
+    vocab_rows = np.asarray(vocab_rows, dtype=np.int64)
+    tokens = np.asarray(tokens).astype(np.int64)
+    c = _f64(coeff)
+    z = H64 @ Wr.T                                            # [t, selected v]
+    g = -np.exp(z - _f64(lse)[:, None])
+    g += (tokens[:, None] == vocab_rows[None, :])             # the one-hot term
+    g *= c[:, None]
+    return g.T @ H64
 
 
 def oapl_forward_backward(H, W, tokens, logq, seq_offsets, rewards, group_ids,

@@ -467,6 +467,19 @@ def test_gradient_invariants():
     rows = np.array([0, 7, 19])
     g = orc.grad_hidden_rows(H, W, tok, res["coeff"], rows)
     assert np.allclose(g, res["dH"][rows], atol=1e-14)
+    # ... and so is the row-wise weight gradient (every vocabulary row, in one piece and summed over
+    # two slabs of token rows, each with its own slice of the per-token inputs)
+    vsel = np.array([0, 3, 10, 5])
+    gw = orc.grad_weight_rows(H, W[vsel], vsel, tok, res["coeff"], res["lse"])
+    assert np.allclose(gw, res["dW"][vsel], atol=1e-13)
+    cut = 9
+    gw2 = (orc.grad_weight_rows(H[:cut], W[vsel], vsel, tok[:cut], res["coeff"][:cut], res["lse"][:cut]) +
+           orc.grad_weight_rows(H[cut:], W[vsel], vsel, tok[cut:], res["coeff"][cut:], res["lse"][cut:]))
+    assert np.allclose(gw2, res["dW"][vsel], atol=1e-13)
+    allv = np.arange(W.shape[0])
+    assert np.allclose(orc.grad_weight_rows(H, W, allv, tok, res["coeff"], res["lse"]), res["dW"], atol=1e-13)
+    # a dropped one-hot term or a sign slip would not survive this: rows of sampled tokens differ from the rest
+    assert set(tok) & set(vsel)
 
 
 def test_rollouts_with_zero_residual_get_zero_gradient():
