@@ -59,6 +59,9 @@ def parse():
                     help="loss: the whole hot path (default). logprob / logprob_entropy: oapl_logprob_fwd alone, "
                          "without / with the policy-entropy output (forward scoring only). "
                          "sample: oapl_sample_tokens (Gumbel-max draws at the workload's token temperature)")
+    ap.add_argument("--panel-rows", type=int, default=0,
+                    help="size the workspace for backward panels of at most this many token rows (0 = the "
+                         "library's default); the library derives its panel from the workspace it is handed")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-tokens", type=int, default=2048)
     ap.add_argument("--calibration-copy", action="store_true",
@@ -119,8 +122,11 @@ def main():
     batch = synth.make_batch(cfg, dev)
     T, d, V = batch.T, cfg.d, cfg.V
     dt_code = oapl.OAPL_BF16 if cfg.dtype == "bf16" else oapl.OAPL_F32
-    ws = torch.empty(oapl.workspace_bytes(T, d, V, batch.n_seq, batch.n_groups, dt_code, cfg.backward),
-                     dtype=torch.uint8, device=dev)
+    # the trainer knows its generation limit: panel buffers for the longest rollout of the workload
+    longest = int((batch.seq_offsets[1:] - batch.seq_offsets[:-1]).max().item()) if batch.n_seq else 0
+    ws_bytes, panel_rows, panel_buffers = oapl.workspace_bytes_for(T, d, V, batch.n_seq, batch.n_groups, dt_code,
+                                                                   cfg.backward, args.panel_rows, longest)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
     dH = torch.empty_like(batch.H) if cfg.backward else None
     dW = torch.empty((V, d), dtype=torch.float32, device=dev) if cfg.backward else None
 
@@ -209,6 +215,8 @@ def main():
         "algorithmic_tflops": alg_tflops, "frac_of_bf16_peak_algorithmic": alg_tflops / PEAK_BF16_TFLOPS,
         "executed_tflops": hw_tflops, "frac_of_bf16_peak_executed": hw_tflops / PEAK_BF16_TFLOPS,
         "schedule": ("two_pass" if two_pass else "single_sweep") if backward else "forward_only",
+        "workspace_bytes": ws_bytes, "panel_rows": panel_rows if backward else None,
+        "panel_buffers": panel_buffers if backward else None, "longest_rollout": longest,
         "kernels": kernels, "roofline": roofline, "loss" if args.path in ("loss", "grpo") else "output_checksum": loss,
     }
     if not args.no_cpu_baseline and args.path == "loss":

@@ -26,8 +26,8 @@
  *     oapl_read_device_status.
  *   - Inputs are never modified; outputs are fully overwritten.
  *   - `workspace` must hold at least oapl_workspace_bytes(...) bytes for the
- *     same sizes, aligned to 256 bytes (the loss calls also accept less, see
- *     oapl_workspace_bytes_for_panel).  Its contents are scratch.  Two calls
+ *     same sizes, aligned to 256 bytes (the loss calls also accept less or more,
+ *     see oapl_workspace_bytes_for).  Its contents are scratch.  Two calls
  *     may run concurrently only with distinct workspaces.  The library keeps
  *     no state between calls: there are no process-wide switches.
  *   - The return value is an oapl_status.  Errors the host can see (null
@@ -96,25 +96,32 @@ size_t oapl_workspace_bytes(int64_t T, int32_t d, int32_t V, int32_t n_seq,
  * The workspace is the memory budget of a loss call.  The gradients are
  * produced panel by panel (a panel = a range of token rows whose soft-max
  * values are held, bf16, until the dH and dW contractions have consumed them),
- * and nearly all of the workspace is panel storage, proportional to the panel's
- * rows.  oapl_workspace_bytes sizes it for the library's default panel (the
- * fastest: at most 61440 rows for OAPL_BF16, 4096 for OAPL_F32).  This call
- * returns the bytes needed when panels are at most max_panel_rows rows
- * (rounded down to whole 384-row tiles for OAPL_BF16, at least one tile;
- * <= 0 or above the default = the default) and stores the panel size the plan
- * then uses in *panel_rows_out (host pointer, may be NULL).
+ * and nearly all of the workspace is panel storage: panel rows x V x 4 bytes
+ * per panel buffer.  Two things can be chosen:
+ *   - the panel size.  oapl_workspace_bytes uses the library's own (at most
+ *     12288 rows for OAPL_BF16 -- the fastest measured -- and 4096 for
+ *     OAPL_F32); max_panel_rows caps it lower (rounded down to whole 384-row
+ *     tiles for OAPL_BF16, at least one tile; <= 0 or larger = the library's);
+ *   - the number of panel buffers (OAPL_BF16).  The single sweep finishes a
+ *     panel's gradients only when every rollout touching it is scored, so it
+ *     keeps a ring of panels: 1 + ceil(longest rollout / panel rows) buffers
+ *     serve rollouts of that length.  oapl_workspace_bytes sizes two buffers
+ *     (rollouts up to one panel); pass max_rollout_len to size more (<= 0 =
+ *     two).  Longer rollouts than the buffers serve are not an error: the call
+ *     then takes the two-pass schedule (decided on the device).
+ * Returns the bytes needed, and the panel rows / buffers of that plan through
+ * the host pointers (each may be NULL).  Returns 0 for invalid sizes.
  *
- * A loss call handed a workspace smaller than oapl_workspace_bytes(...) uses
- * the largest panel whose plan fits workspace_bytes, and fails with
- * OAPL_ERR_WORKSPACE only if not even a one-tile panel fits.  Results do not
- * depend on the panel size beyond rounding (summation order of dW over
- * panels).  The single sweep additionally needs every rollout to be at most
- * one panel long; with smaller panels and longer rollouts the call takes the
- * two-pass schedule (decided on the device).
+ * A loss call derives its plan from workspace_bytes alone: the library's panel
+ * size if two buffers of it fit, else the largest panel that does
+ * (OAPL_ERR_WORKSPACE if not even a one-tile panel fits); then as many buffers
+ * as fit.  Results do not depend on the plan beyond rounding (summation order
+ * of dW over panels).
  */
-size_t oapl_workspace_bytes_for_panel(int64_t T, int32_t d, int32_t V, int32_t n_seq,
-                                      int32_t n_groups, int32_t dtype, int32_t with_backward,
-                                      int64_t max_panel_rows, int64_t* panel_rows_out);
+size_t oapl_workspace_bytes_for(int64_t T, int32_t d, int32_t V, int32_t n_seq,
+                                int32_t n_groups, int32_t dtype, int32_t with_backward,
+                                int64_t max_panel_rows, int64_t max_rollout_len,
+                                int64_t* panel_rows_out, int32_t* panel_buffers_out);
 
 /*
  * Per-token log-probability of the sampled token under pi (the ln pi(y_t | x,
@@ -183,11 +190,12 @@ int32_t oapl_sample_tokens(const void* H, const void* W, int64_t T, int32_t d, i
  *               dW[v,:] = sum_t c_t (1[v = y_t] - p_{t,v}) H[t,:]
  *
  * How the gradients are scheduled (bf16): the logits are visited ONCE.  Panels of
- * token rows (at most 61440, fewer if the workspace is smaller) are swept with the soft-max written unnormalised
- * (bf16, against a per-row reference exponent fixed before the sweep), their
- * row sums give lse and the log-probs, and the dH / dW contractions consume a
- * panel as soon as every rollout touching it is scored.  That needs (a) no
- * rollout longer than one panel and (b) every row's largest logit within
+ * token rows (12288 by default, see oapl_workspace_bytes_for) are swept with the
+ * soft-max written unnormalised (bf16, against a per-row reference exponent
+ * fixed before the sweep), their row sums give lse and the log-probs, and the
+ * dH / dW contractions consume a panel as soon as every rollout touching it is
+ * scored.  That needs (a) no rollout longer than the panel buffers serve (one
+ * panel with the default workspace) and (b) every row's largest logit within
  * about 97 nats of the largest among its first 256 vocabulary entries and the
  * sampled token.  Both are checked on the device; if either fails, the same
  * call recomputes everything in two passes (log-sum-exp first, then soft-max

@@ -85,4 +85,15 @@ __device__ __forceinline__ int xcd_logical_id(int bid, int total) {
   return (bid & 7) * per + (bid >> 3);
 }
 
+// The other way to keep neighbours in one L2: the 256 workgroups that run together (one per CU)
+// take 256 consecutive logical ids, 32 per XCD, round after round, so that at any moment ALL XCDs
+// work on neighbouring tiles and read the shared operand panels at about the same time (what one
+// XCD fetched from HBM the others find in the memory-side cache).  Launch round_up(total, 256)
+// workgroups and drop ids >= total.  Measured: +3.5 % on the dW contraction (whose m-side operand,
+// the panel's transposed hidden states, is shared by every tile), nothing on dH, -1..-4 % on the sweep.
+__device__ __forceinline__ int xcd_round_major_id(int bid) {
+  const int j = bid >> 3;
+  return (j >> 5) * 256 + (bid & 7) * 32 + (j & 31);
+}
+
 }  // namespace oapl

@@ -969,7 +969,7 @@ k_bwd_dw(const bf16_t* __restrict__ HTp, const bf16_t* __restrict__ GTp, int t_n
   const int MT = (d + C::BM - 1) / C::BM;
   const int NTl = (V + C::BN - 1) / C::BN;
   const int total = MT * NTl;
-  const int L = xcd_logical_id(blockIdx.x, total);
+  const int L = xcd_round_major_id(blockIdx.x);   // launched in whole rounds of 256 workgroups
   if (L >= total) return;
   int mt, nt;
   strip_tile<4>(L, MT, NTl, mt, nt);

@@ -24,7 +24,12 @@ static_assert(Cfg::BN == kPackRowsB, "n-side operands of the loss path are packe
 // with H packed in 256-row blocks for it.
 typedef TileCfg<4, 2, 2, 4, 2> CfgSample;
 
-constexpr int64_t kPanelBf16 = 61440;  // most token rows per backward panel (bf16 path): 160 token tiles
+// Most token rows per backward panel (bf16 path): 32 token tiles, the fastest size measured (the dH
+// contraction then has d / 256 x 32 tiles, whole rounds of 256 workgroups for d a multiple of 2048;
+// larger panels run 2 .. 3 % slower, smaller ones pay more for the read-add-write of dW).  A smaller
+// workspace makes panels smaller; a larger one buys more panel buffers (longer rollouts on the single
+// sweep), never larger panels.
+constexpr int64_t kPanelBf16 = 12288;
 constexpr int64_t kPanelF32 = 4096;    // ... (fp32 path)
 constexpr int64_t kGroupScanLimit = (int64_t)1 << 32;   // n_seq * n_groups: every prompt's wavefront walks all rollouts
 constexpr int kStatusWords = 64;       // 256-byte header
@@ -39,13 +44,15 @@ struct Plan {
   int n_parts = 0;     // soft-max partials per token
   int n_parts_s = 0;   // (score, index) partials per token of the sampling kernel
   int64_t Tp = 0;      // rows of one backward panel
+  int n_buf = 1;       // panel buffers of the single sweep (a ring; one if the batch is one panel)
+  size_t size_G = 0, size_GT = 0;   // bytes of one panel buffer of each packed copy
   // packed-operand geometry (bf16 path): row tiles and k-blocks (strip pitches)
   int n_rt_v = 0, n_rt_d = 0, n_kt_d = 0, n_kt_v = 0, n_kt_g = 0, n_kt_t = 0;
   int n_rb_v = 0;      // 384-row blocks of a matrix whose rows are the vocabulary (G^T)
   int64_t n_rt_T = 0;  // 384-row token tiles of the whole batch
   size_t off_status = 0, off_partials = 0, off_upart = 0, off_zy = 0, off_lse2 = 0, off_diff = 0, off_coef = 0, off_delta = 0,
          off_cseq = 0, off_vstar = 0, off_gw = 0, off_omp = 0, off_inv = 0, off_Wp = 0, off_Hp = 0, off_WTp = 0, off_HTp = 0,
-         off_G = 0, off_GT = 0, off_ref2 = 0, off_spart = 0, off_G2 = 0, off_GT2 = 0, total = 0;
+         off_G = 0, off_GT = 0, off_ref2 = 0, off_spart = 0, total = 0;
   bool sweep = false;  // single-sweep loss path available (bf16 with backward)
 };
 
@@ -55,8 +62,8 @@ constexpr int kFlagWord = 8;   // status word that selects the two-pass path on 
 // they show in the gradient norm.  Smaller batches take the two-pass path, whose one-hot entry is exact.
 constexpr int64_t kSweepMinTokens = 64;
 
-// Largest panel the plan may use: `max_panel_rows` <= 0 means the library's default cap; other
-// values are rounded down to whole token tiles (bf16), with one tile as the least.
+// Largest panel the plan may use: `max_panel_rows` <= 0 or above the library's size means that
+// size; other values are rounded down to whole token tiles (bf16), with one tile as the least.
 static int64_t panel_cap(int dtype, int64_t max_panel_rows) {
   const int64_t deflt = dtype == OAPL_BF16 ? kPanelBf16 : kPanelF32;
   if (max_panel_rows <= 0 || max_panel_rows > deflt) return deflt;
@@ -64,8 +71,10 @@ static int64_t panel_cap(int dtype, int64_t max_panel_rows) {
   return max_panel_rows < Cfg::BN ? Cfg::BN : max_panel_rows / Cfg::BN * Cfg::BN;
 }
 
+// `panel_buffers`: how many panels the single sweep keeps before their gradient contractions run
+// (<= 0: two, the least for a batch of several panels; never more than the batch has panels).
 static bool make_plan(Plan& p, int64_t T, int d, int V, int n_seq, int n_groups, int dtype, bool bwd,
-                      int64_t max_panel_rows = 0) {
+                      int64_t max_panel_rows = 0, int64_t panel_buffers = 0, int64_t exact_panel_rows = 0) {
   if (T < 0 || d < 1 || V < 1 || n_seq < 0 || n_groups < 1) return false;
   if (dtype != OAPL_F32 && dtype != OAPL_BF16) return false;
   if (dtype == OAPL_BF16 && (d % 8) != 0) return false;
@@ -100,13 +109,15 @@ static bool make_plan(Plan& p, int64_t T, int d, int V, int n_seq, int n_groups,
     };
     p.n_parts = pick_splits(n_tiles);
     p.n_parts_s = pick_splits((T + CfgSample::BN - 1) / CfgSample::BN);
-    // Panel size: a multiple of the token tile, at most kPanelBf16 rows.  One panel if T fits; otherwise
+    // Panel size: a multiple of the token tile, at most `cap` rows.  One panel if T fits; otherwise
     // the size (between half the cap and the cap) that costs the fewest rounds of kNumCU workgroups in
     // the dH contraction -- its tiles (d / 256 x panel rows / 384, each K = V long) are few and long, so
     // a partly filled last round is expensive -- plus a charge per panel for the fp32 read-add-write
     // pass over dW.  Ties go to the larger panel (longer rollouts fit the single sweep).
     if (T <= cap) {
       p.Tp = round_up(T > 0 ? T : 1, Cfg::BN);
+    } else if (exact_panel_rows > 0) {   // a size an earlier plan for the same shapes chose
+      p.Tp = exact_panel_rows;
     } else {
       const int64_t mtd = (d + Cfg::BM - 1) / Cfg::BM;
       const int64_t k_max = cap / Cfg::BN;
@@ -161,17 +172,19 @@ static bool make_plan(Plan& p, int64_t T, int d, int V, int n_seq, int n_groups,
     if (dtype == OAPL_BF16) {
       p.off_WTp = take((size_t)p.n_rt_d * p.n_kt_v * kPackBlockBytesA);
       p.off_HTp = take((size_t)p.n_rt_d * p.n_kt_t * kPackBlockBytesA);
-      p.off_G = take((size_t)(p.Tp / Cfg::BN) * p.n_kt_g * kPackBlockBytesB);
-      p.off_GT = take((size_t)p.n_rb_v * p.n_kt_t * kPackBlockBytesB);
-      // single-sweep path: reference exponents, per-vocabulary-tile row sums of one panel, and a
-      // second panel buffer pair (a panel's gradient contractions run after the next panel's sweep)
+      // Panel buffers, both packed copies.  The single sweep keeps a ring of them: a panel's gradient
+      // contractions run once every rollout that touches it is scored, i.e. n_buf - 1 panels later, so
+      // rollouts of up to (n_buf - 1) panels are served (the two-pass schedule uses the first buffer only).
+      const int64_t n_panels = (T + p.Tp - 1) / p.Tp;
+      p.n_buf = (int)(n_panels <= 1 ? 1 : (panel_buffers < 2 ? 2 : (panel_buffers > n_panels ? n_panels : panel_buffers)));
+      p.size_G = ((size_t)(p.Tp / Cfg::BN) * p.n_kt_g * kPackBlockBytesB + 255) / 256 * 256;
+      p.size_GT = ((size_t)p.n_rb_v * p.n_kt_t * kPackBlockBytesB + 255) / 256 * 256;
+      p.off_G = take(p.size_G * p.n_buf);
+      p.off_GT = take(p.size_GT * p.n_buf);
+      // single-sweep path: reference exponents and per-vocabulary-tile row sums of one panel
       p.sweep = true;
       p.off_ref2 = take(Tn * 4);
       p.off_spart = take((size_t)p.n_rt_v * (size_t)p.Tp * 4);
-      if (T > p.Tp) {
-        p.off_G2 = take((size_t)(p.Tp / Cfg::BN) * p.n_kt_g * kPackBlockBytesB);
-        p.off_GT2 = take((size_t)p.n_rb_v * p.n_kt_t * kPackBlockBytesB);
-      }
     } else {
       p.off_G = take((size_t)p.Tp * V * 4);
     }
@@ -368,7 +381,7 @@ static int backward_grads(const Plan& p, const void* H, const void* W, const int
       OAPL_LAUNCH_CHECK();
       {
         ScopedKernelTimer tm(kBwdDw, st, timed);
-        k_bwd_dw<Cfg><<<(unsigned)round_up((int64_t)MTd * NTv, 8), Cfg::NT, Cfg::LDS_BYTES, st>>>(
+        k_bwd_dw<Cfg><<<(unsigned)round_up((int64_t)MTd * NTv, kNumCU), Cfg::NT, Cfg::LDS_BYTES, st>>>(
             HTp, GT, p.n_kt_t, d, V, (int)(Kt / kPackK), dW, t0 > 0 ? 1 : 0, gate);
       }
       OAPL_LAUNCH_CHECK();
@@ -422,8 +435,8 @@ static int sweep_path(const Plan& p, const void* H, const void* W, const int32_t
   const bf16_t* Hp = (const bf16_t*)(ws + p.off_Hp);
   bf16_t* WTp = (bf16_t*)(ws + p.off_WTp);
   bf16_t* HTp = (bf16_t*)(ws + p.off_HTp);
-  bf16_t* Gbuf[2] = {(bf16_t*)(ws + p.off_G), (bf16_t*)(ws + (T > p.Tp ? p.off_G2 : p.off_G))};
-  bf16_t* GTbuf[2] = {(bf16_t*)(ws + p.off_GT), (bf16_t*)(ws + (T > p.Tp ? p.off_GT2 : p.off_GT))};
+  auto Gbuf = [&](int64_t k) { return (bf16_t*)(ws + p.off_G + (size_t)(k % p.n_buf) * p.size_G); };
+  auto GTbuf = [&](int64_t k) { return (bf16_t*)(ws + p.off_GT + (size_t)(k % p.n_buf) * p.size_GT); };
   float2* sample = (float2*)(ws + p.off_partials);
   const float* zy = (const float*)(ws + p.off_zy);
   float* ref2 = (float*)(ws + p.off_ref2);
@@ -436,7 +449,9 @@ static int sweep_path(const Plan& p, const void* H, const void* W, const int32_t
   const int64_t strip_d = (int64_t)p.n_kt_d * (kPackBlockBytesB / 2);   // one token tile of packed H
   const int64_t n_tiles = (T + Cfg::BN - 1) / Cfg::BN;
 
-  k_sweep_plan<<<grid1d(p.n_seq > 0 ? p.n_seq : 1, 256), 256, 0, st>>>(seq_offsets, p.n_seq, T, p.Tp, flag);
+  // a rollout may span at most n_buf - 1 panels' worth of rows (any length if the batch is one panel)
+  k_sweep_plan<<<grid1d(p.n_seq > 0 ? p.n_seq : 1, 256), 256, 0, st>>>(
+      seq_offsets, p.n_seq, T, p.n_buf > 1 ? (int64_t)(p.n_buf - 1) * p.Tp : p.Tp, flag);
   OAPL_LAUNCH_CHECK();
   k_pack_transposed<<<dim3(p.n_kt_v, p.n_rt_d), 256, 0, st>>>((const bf16_t*)W, V, d, d, nullptr, WTp, p.n_kt_v,
                                                               kNoGate);
@@ -466,13 +481,13 @@ static int sweep_path(const Plan& p, const void* H, const void* W, const int32_t
     {
       ScopedKernelTimer tm(kBwdDh, st);
       k_bwd_dh<Cfg><<<(unsigned)round_up(MTd * NTl, 8), Cfg::NT, Cfg::LDS_BYTES, st>>>(
-          WTp, p.n_kt_v, Gbuf[k & 1], p.n_kt_g, d, nv, p.n_kt_v, coef + t0, (bf16_t*)dH + t0 * d, fast);
+          WTp, p.n_kt_v, Gbuf(k), p.n_kt_g, d, nv, p.n_kt_v, coef + t0, (bf16_t*)dH + t0 * d, fast);
     }
     OAPL_LAUNCH_CHECK();
     {
       ScopedKernelTimer tm(kBwdDw, st);
-      k_bwd_dw<Cfg><<<(unsigned)round_up((int64_t)MTd * NTv, 8), Cfg::NT, Cfg::LDS_BYTES, st>>>(
-          HTp, GTbuf[k & 1], p.n_kt_t, d, V, (int)(Kt / kPackK), dW, k > 0 ? 1 : 0, fast);
+      k_bwd_dw<Cfg><<<(unsigned)round_up((int64_t)MTd * NTv, kNumCU), Cfg::NT, Cfg::LDS_BYTES, st>>>(
+          HTp, GTbuf(k), p.n_kt_t, d, V, (int)(Kt / kPackK), dW, k > 0 ? 1 : 0, fast);
     }
     OAPL_LAUNCH_CHECK();
     return OAPL_OK;
@@ -484,18 +499,20 @@ static int sweep_path(const Plan& p, const void* H, const void* W, const int32_t
     {
       ScopedKernelTimer tm(kSweep, st);
       k_sweep<Cfg><<<(unsigned)round_up(MTv * NTl, 8), Cfg::NT, Cfg::LDS_BYTES, st>>>(
-          Wp, Hp + (t0 / Cfg::BN) * strip_d, V, nv, p.n_kt_d, ref2 + t0, Gbuf[k & 1], p.n_kt_g, GTbuf[k & 1],
+          Wp, Hp + (t0 / Cfg::BN) * strip_d, V, nv, p.n_kt_d, ref2 + t0, Gbuf(k), p.n_kt_g, GTbuf(k),
           p.n_kt_t, spart, p.Tp, fast);
     }
     OAPL_LAUNCH_CHECK();
     k_sweep_finish<<<grid1d(nv, 256), 256, 0, st>>>(spart, MTv, p.Tp, nv, ref2 + t0, zy + t0, logq + t0, tokens + t0,
                                                     V, logprob_out ? logprob_out + t0 : nullptr, diff + t0, nis + t0,
-                                                    Gbuf[k & 1], p.n_kt_g, GTbuf[k & 1], p.n_kt_t, flag, fast);
+                                                    Gbuf(k), p.n_kt_g, GTbuf(k), p.n_kt_t, flag, fast);
     OAPL_LAUNCH_CHECK();
-    if (k >= 1)
-      if (int rc = gradients(k - 1)) return rc;
+    if (k >= p.n_buf - 1 && p.n_buf > 1)
+      if (int rc = gradients(k - (p.n_buf - 1))) return rc;
   }
-  return gradients(n_panels - 1);
+  for (int64_t k = n_panels - (p.n_buf > 1 ? p.n_buf - 1 : 1); k < n_panels; ++k)
+    if (int rc = gradients(k)) return rc;
+  return OAPL_OK;
 }
 
 static int check_workspace(const void* ws, size_t have, size_t need) {
@@ -503,23 +520,36 @@ static int check_workspace(const void* ws, size_t have, size_t need) {
   return OAPL_OK;
 }
 
-// The plan of a loss call: the workspace the caller hands over is the budget.  The default plan
-// if it fits; otherwise the largest backward panel (whole token tiles for bf16) whose plan does.
+// The plan of a loss call: the workspace the caller hands over is the budget.  Panel size first:
+// the default panel (the fastest) if two buffers of it fit, else the largest that does.  Then as
+// many panel buffers as fit (and the batch has panels): they decide how long a rollout the single
+// sweep serves, not how fast it runs.
 static int fit_plan(Plan& p, int64_t T, int d, int V, int n_seq, int n_groups, int dtype, bool bwd, const void* ws,
                     size_t have) {
   if (!make_plan(p, T, d, V, n_seq, n_groups, dtype, bwd)) return OAPL_ERR_SHAPE;
   if (ws == nullptr || ((uintptr_t)ws & 255) != 0) return OAPL_ERR_WORKSPACE;
-  if (p.total <= have) return OAPL_OK;
-  if (!bwd) return OAPL_ERR_WORKSPACE;
-  const int64_t step = dtype == OAPL_BF16 ? Cfg::BN : 64;
-  for (int64_t rows = (p.Tp - 1) / step * step; rows >= step; rows -= step) {
-    Plan q;
-    if (make_plan(q, T, d, V, n_seq, n_groups, dtype, bwd, rows) && q.total <= have) {
-      p = q;
-      return OAPL_OK;
+  if (!bwd) return p.total <= have ? OAPL_OK : OAPL_ERR_WORKSPACE;
+  if (p.total > have) {
+    const int64_t step = dtype == OAPL_BF16 ? Cfg::BN : 64;
+    bool found = false;
+    for (int64_t rows = (p.Tp - 1) / step * step; rows >= step && !found; rows -= step) {
+      Plan q;
+      if (make_plan(q, T, d, V, n_seq, n_groups, dtype, bwd, rows) && q.total <= have) {
+        p = q;
+        found = true;
+      }
+    }
+    if (!found) return OAPL_ERR_WORKSPACE;
+  }
+  if (p.sweep && p.n_buf >= 2) {
+    const size_t per_buffer = p.size_G + p.size_GT;
+    const int64_t extra = (int64_t)((have - p.total) / per_buffer);
+    if (extra > 0) {
+      Plan q;
+      if (make_plan(q, T, d, V, n_seq, n_groups, dtype, bwd, p.Tp, p.n_buf + extra, p.Tp) && q.total <= have) p = q;
     }
   }
-  return OAPL_ERR_WORKSPACE;
+  return OAPL_OK;
 }
 
 static int loss_impl(const void* H, const void* W, const int32_t* tokens, const float* logq,
@@ -712,12 +742,19 @@ size_t oapl_workspace_bytes(int64_t T, int32_t d, int32_t V, int32_t n_seq, int3
   return p.total;
 }
 
-size_t oapl_workspace_bytes_for_panel(int64_t T, int32_t d, int32_t V, int32_t n_seq, int32_t n_groups,
-                                      int32_t dtype, int32_t with_backward, int64_t max_panel_rows,
-                                      int64_t* panel_rows_out) {
+size_t oapl_workspace_bytes_for(int64_t T, int32_t d, int32_t V, int32_t n_seq, int32_t n_groups, int32_t dtype,
+                                int32_t with_backward, int64_t max_panel_rows, int64_t max_rollout_len,
+                                int64_t* panel_rows_out, int32_t* panel_buffers_out) {
   Plan p;
   if (!make_plan(p, T, d, V, n_seq, n_groups, dtype, with_backward != 0, max_panel_rows)) return 0;
+  if (max_rollout_len > p.Tp && p.n_buf >= 2) {   // buffers for the longest rollout: 1 + ceil(len / panel)
+    const int64_t want = 1 + (max_rollout_len + p.Tp - 1) / p.Tp;
+    Plan q;
+    if (!make_plan(q, T, d, V, n_seq, n_groups, dtype, with_backward != 0, p.Tp, want, p.Tp)) return 0;
+    p = q;
+  }
   if (panel_rows_out) *panel_rows_out = p.Tp;
+  if (panel_buffers_out) *panel_buffers_out = p.n_buf;
   return p.total;
 }
 

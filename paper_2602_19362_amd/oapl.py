@@ -32,8 +32,9 @@ _SIGNATURES = {
     "oapl_status_string": (_c.c_char_p, [_c.c_int32]),
     "oapl_workspace_bytes": (_c.c_size_t, [_c.c_int64, _c.c_int32, _c.c_int32, _c.c_int32, _c.c_int32, _c.c_int32,
                                            _c.c_int32]),
-    "oapl_workspace_bytes_for_panel": (_c.c_size_t, [_c.c_int64, _c.c_int32, _c.c_int32, _c.c_int32, _c.c_int32,
-                                                     _c.c_int32, _c.c_int32, _c.c_int64, _c.POINTER(_c.c_int64)]),
+    "oapl_workspace_bytes_for": (_c.c_size_t, [_c.c_int64, _c.c_int32, _c.c_int32, _c.c_int32, _c.c_int32,
+                                               _c.c_int32, _c.c_int32, _c.c_int64, _c.c_int64,
+                                               _c.POINTER(_c.c_int64), _c.POINTER(_c.c_int32)]),
     "oapl_logprob_fwd": (_c.c_int32, [_c.c_void_p, _c.c_void_p, _c.c_void_p, _c.c_int64, _c.c_int32, _c.c_int32,
                                       _c.c_int32, _c.c_void_p, _c.c_void_p, _c.c_void_p, _c.c_void_p, _c.c_size_t,
                                       _c.c_void_p]),
@@ -117,20 +118,23 @@ def _stream(device) -> int:
 
 
 def workspace_bytes(T: int, d: int, V: int, n_seq: int, n_groups: int, dtype: int, with_backward: bool,
-                    max_panel_rows: Optional[int] = None) -> int:
-    """oapl_workspace_bytes, or oapl_workspace_bytes_for_panel when a panel cap is given."""
-    if max_panel_rows is None:
+                    max_panel_rows: Optional[int] = None, max_rollout_len: Optional[int] = None) -> int:
+    """oapl_workspace_bytes, or oapl_workspace_bytes_for when a panel cap or a rollout length is given."""
+    if max_panel_rows is None and max_rollout_len is None:
         return int(lib().oapl_workspace_bytes(T, d, V, n_seq, n_groups, dtype, 1 if with_backward else 0))
-    return workspace_bytes_for_panel(T, d, V, n_seq, n_groups, dtype, with_backward, max_panel_rows)[0]
+    return workspace_bytes_for(T, d, V, n_seq, n_groups, dtype, with_backward, max_panel_rows or 0,
+                               max_rollout_len or 0)[0]
 
 
-def workspace_bytes_for_panel(T: int, d: int, V: int, n_seq: int, n_groups: int, dtype: int, with_backward: bool,
-                              max_panel_rows: int):
-    """oapl_workspace_bytes_for_panel: (bytes, panel rows the plan uses)."""
+def workspace_bytes_for(T: int, d: int, V: int, n_seq: int, n_groups: int, dtype: int, with_backward: bool,
+                        max_panel_rows: int = 0, max_rollout_len: int = 0):
+    """oapl_workspace_bytes_for: (bytes, panel rows, panel buffers) of the plan."""
     rows = ctypes.c_int64(0)
-    n = lib().oapl_workspace_bytes_for_panel(T, d, V, n_seq, n_groups, dtype, 1 if with_backward else 0,
-                                             int(max_panel_rows), ctypes.byref(rows))
-    return int(n), int(rows.value)
+    bufs = ctypes.c_int32(0)
+    n = lib().oapl_workspace_bytes_for(T, d, V, n_seq, n_groups, dtype, 1 if with_backward else 0,
+                                       int(max_panel_rows), int(max_rollout_len), ctypes.byref(rows),
+                                       ctypes.byref(bufs))
+    return int(n), int(rows.value), int(bufs.value)
 
 
 def _workspace(nbytes: int, device, workspace: Optional[torch.Tensor]) -> torch.Tensor:
@@ -234,12 +238,12 @@ class LossResult(NamedTuple):
 def loss_fwd_bwd(H, W, tokens, logq, seq_offsets, rewards, group_ids, n_groups: int, beta: float, *,
                  beta_value: Optional[float] = None, loss_scale: float = 1.0, backward: bool = True,
                  two_pass: bool = False, max_panel_rows: Optional[int] = None,
-                 workspace: Optional[torch.Tensor] = None, dH: Optional[torch.Tensor] = None,
-                 dW: Optional[torch.Tensor] = None) -> LossResult:
+                 max_rollout_len: Optional[int] = None, workspace: Optional[torch.Tensor] = None,
+                 dH: Optional[torch.Tensor] = None, dW: Optional[torch.Tensor] = None) -> LossResult:
     """oapl_loss_fwd_bwd (or the two-beta entry point when beta_value or two_pass is given).
 
-    max_panel_rows only sizes the workspace this wrapper allocates when none is passed; the
-    library derives the panel from the bytes it is handed.
+    max_panel_rows / max_rollout_len only size the workspace this wrapper allocates when none is
+    passed; the library derives its plan from the bytes it is handed.
     """
     L = lib()
     _check_device(H)
@@ -251,7 +255,7 @@ def loss_fwd_bwd(H, W, tokens, logq, seq_offsets, rewards, group_ids, n_groups: 
             or group_ids.shape != (n_seq,):
         raise ValueError("shape mismatch between the inputs")
     dev = H.device
-    nbytes = workspace_bytes(T, d, V, n_seq, n_groups, dt, backward, max_panel_rows)
+    nbytes = workspace_bytes(T, d, V, n_seq, n_groups, dt, backward, max_panel_rows, max_rollout_len)
     if nbytes == 0:
         raise OaplError(2, "oapl_workspace_bytes")
     ws = _workspace(nbytes, dev, workspace)
@@ -325,8 +329,8 @@ class GrpoResult(NamedTuple):
 def grpo_loss_fwd_bwd(H, W, tokens, logq, logp_old, seq_offsets, rewards, group_ids, n_groups: int, *,
                       clip_eps: float = 0.2, adv_eps: float = 1e-6, loss_scale: float = 1.0, backward: bool = True,
                       two_pass: bool = False, max_panel_rows: Optional[int] = None,
-                      workspace: Optional[torch.Tensor] = None, dH: Optional[torch.Tensor] = None,
-                      dW: Optional[torch.Tensor] = None) -> GrpoResult:
+                      max_rollout_len: Optional[int] = None, workspace: Optional[torch.Tensor] = None,
+                      dH: Optional[torch.Tensor] = None, dW: Optional[torch.Tensor] = None) -> GrpoResult:
     """oapl_grpo_loss_fwd_bwd: the paper's GRPO + token-level importance sampling baseline."""
     _check_device(H)
     dt = _dtype_code(H)
@@ -337,7 +341,7 @@ def grpo_loss_fwd_bwd(H, W, tokens, logq, logp_old, seq_offsets, rewards, group_
             or seq_offsets.shape != (n_seq + 1,) or group_ids.shape != (n_seq,):
         raise ValueError("shape mismatch between the inputs")
     dev = H.device
-    nbytes = workspace_bytes(T, d, V, n_seq, n_groups, dt, backward, max_panel_rows)
+    nbytes = workspace_bytes(T, d, V, n_seq, n_groups, dt, backward, max_panel_rows, max_rollout_len)
     if nbytes == 0:
         raise OaplError(2, "oapl_workspace_bytes")
     ws = _workspace(nbytes, dev, workspace)

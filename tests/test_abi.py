@@ -39,14 +39,16 @@ def test_workspace_bytes_host_logic():
     assert small > 0 and small % 256 == 0
     assert wb(256, 64, 1024, 8, 2, oapl.OAPL_F32, True) > small
     # the bf16 backward workspace holds one pair of soft-max panels (tokens x V and V x tokens) when
-    # T fits one panel (at most 61440 rows) and two pairs beyond that; they stop growing at the panel
-    # size, after which only the per-token buffers and the packed copy of H grow with T
-    panel = 61440 * 151936 * 2
-    a = wb(61440, 4096, 151936, 64, 8, oapl.OAPL_BF16, True)
+    # T fits one panel (at most 12288 rows by default) and two pairs beyond that; they stop growing at
+    # the panel size, after which only the per-token buffers and the packed copy of H grow with T
+    panel = 12288 * 151936 * 2
+    a = wb(12288, 4096, 151936, 64, 8, oapl.OAPL_BF16, True)
     b = wb(1 << 20, 4096, 151936, 64, 8, oapl.OAPL_BF16, True)
     c = wb(1 << 21, 4096, 151936, 64, 8, oapl.OAPL_BF16, True)
-    assert 2 * panel < a < 3 * panel and 4 * panel < b < 5 * panel
-    assert c - b < (1 << 20) * (2 * 4096 + 2048)      # packed H row + per-token scalars and soft-max partials
+    per_token = 2 * 4096 + 2048                       # packed H row + per-token scalars and soft-max partials
+    assert 2 * panel < a < 3 * panel
+    assert 2 * panel < b - a < 2 * panel + (1 << 20) * per_token
+    assert c - b < (1 << 20) * per_token
     # invalid sizes
     assert wb(-1, 64, 1024, 8, 2, 0, False) == 0
     assert wb(256, 0, 1024, 8, 2, 0, False) == 0
@@ -64,29 +66,36 @@ def test_workspace_bytes_host_logic():
 
 
 def test_workspace_is_the_memory_budget():
-    """oapl_workspace_bytes_for_panel: smaller panels need less workspace, the plan reports its panel."""
-    wbp = oapl.workspace_bytes_for_panel
+    """oapl_workspace_bytes_for: panel size and panel buffers set the workspace; the plan reports both."""
+    wbf = oapl.workspace_bytes_for
     args = (140897, 4096, 151936, 64, 8, oapl.OAPL_BF16, True)
     full = oapl.workspace_bytes(*args)
-    assert wbp(*args, 0) == (full, wbp(*args, 61440)[1]) and wbp(*args, 1 << 40)[0] == full
+    assert wbf(*args, 0, 0) == (full, 12288, 2)                    # default: 32 token tiles, two buffers
+    per_row = 151936 * 2 * 2                                        # both packed copies, bf16
     prev = None
-    for cap in (384, 1000, 6144, 12288, 24576, 61440):
-        nbytes, rows = wbp(*args, cap)
-        assert nbytes > 0 and rows % 384 == 0 and 384 <= rows <= max(cap, 384)
+    for cap in (384, 1000, 6144, 12288, 24576, 1 << 40):
+        nbytes, rows, bufs = wbf(*args, cap, 0)
+        assert nbytes > 0 and rows % 384 == 0 and 384 <= rows <= max(min(cap, 12288), 384) and bufs == 2
+        assert 2 * rows * per_row < nbytes < 2 * rows * per_row * 1.02 + (5 << 30)
         assert prev is None or nbytes >= prev
         prev = nbytes
-    # two panel pairs (tokens x V and V x tokens, bf16) dominate: 4 * rows * V * 2 bytes
-    nbytes, rows = wbp(*args, 12288)
-    assert rows == 12288 and 4 * rows * 151936 * 2 < nbytes < 4 * rows * 151936 * 2 + (5 << 30)
-    assert nbytes < 20 << 30
+    assert full < 18 << 30
+    # buffers for longer rollouts: 1 + ceil(len / panel rows), never more than the batch has panels
+    assert wbf(*args, 0, 12288)[2] == 2 and wbf(*args, 0, 12289)[2] == 3 and wbf(*args, 0, 32768)[2] == 4
+    assert wbf(*args, 0, 10 ** 9)[2] == 12                          # ceil(140897 / 12288) panels in all
+    a3, _, _ = wbf(*args, 0, 12289)
+    assert 0.98 * 12288 * per_row < a3 - full < 1.02 * 12288 * per_row
     # one panel is enough when the batch fits it
-    assert wbp(6000, 4096, 151936, 8, 1, oapl.OAPL_BF16, True, 6144)[1] == 6144
+    assert wbf(6000, 4096, 151936, 8, 1, oapl.OAPL_BF16, True, 0, 50000)[1:] == (6144, 1)
+    # d = 5120: 20 row tiles of dH per token tile; the plan picks a panel that fills whole rounds of 256 workgroups
+    rows = wbf(896842, 5120, 151936, 128, 8, oapl.OAPL_BF16, True, 0, 0)[1]
+    assert rows % 384 == 0 and 6144 <= rows <= 12288 and (20 * rows // 384) % 256 in (0, *range(240, 256))
     # fp32: the panel is the logit-gradient block [rows, V]
-    a, ra = wbp(5000, 64, 1024, 8, 2, oapl.OAPL_F32, True, 0)
-    b, rb = wbp(5000, 64, 1024, 8, 2, oapl.OAPL_F32, True, 512)
+    a, ra, _ = wbf(5000, 64, 1024, 8, 2, oapl.OAPL_F32, True, 0, 0)
+    b, rb, _ = wbf(5000, 64, 1024, 8, 2, oapl.OAPL_F32, True, 512, 0)
     assert (ra, rb) == (4096, 512) and a - b == (4096 - 512) * 1024 * 4
     # invalid sizes answer 0 like oapl_workspace_bytes
-    assert wbp(-1, 64, 1024, 8, 2, 0, True, 512) == (0, 0)
+    assert wbf(-1, 64, 1024, 8, 2, 0, True, 512, 0) == (0, 0, 0)
 
 
 def test_host_side_errors_return_before_any_launch():

@@ -148,22 +148,29 @@ def test_bf16_smallest_shapes(d, V, lens):
 
 
 def test_bf16_several_backward_panels():
-    """T = 150 001 spans three backward panels (61 440 rows, the last one ragged); rollouts 2 and 4
-    straddle the panel boundaries at 61 440 and 122 880."""
-    lens = [50000, 9000, 40000, 233, 50768, 0]
-    b = _custom_batch("bf16", d=64, V=520, lens=lens, n_groups=2, seed=5, beta=1.0, noise=0.02)
+    """T = 49 289 spans five backward panels of 12 288 rows (the last one ragged); rollouts straddle
+    the panel boundaries, one is exactly a panel long."""
+    lens = [12000, 9000, 12288, 233, 10768, 0, 5000]
+    b = _custom_batch("bf16", d=64, V=520, lens=lens, n_groups=1, seed=5, beta=1.0, noise=0.02)
     res = _run(b)
     ref = oracle_full(b)
     _check(b, res, ref, lp_tol=2e-2, rel_tol=1e-3, g_rtol=2e-2, g_atol_frac=6e-3)
 
 
-def test_bf16_rollout_longer_than_a_panel_takes_two_passes():
-    """A 65 536-token rollout does not fit one 61 440-row panel: the device sends the call down the
-    two-pass schedule, with the same results."""
-    lens = [65536, 9000, 40000, 233, 35232, 0]
+def test_bf16_default_panels_with_a_ring_of_buffers_for_long_rollouts():
+    """The same batch at the default panel size (12 288 rows, 13 panels): its 50 768-token rollout
+    needs 1 + ceil(50768 / 12288) = 6 panel buffers to stay on the single sweep; with the default two
+    buffers the device sends the call down the two-pass schedule.  Same results either way."""
+    lens = [50000, 9000, 40000, 233, 50768, 0]
     b = _custom_batch("bf16", d=64, V=520, lens=lens, n_groups=2, seed=5, beta=1.0, noise=0.02)
-    res = _run(b)
     ref = oracle_full(b)
+    assert oapl.workspace_bytes_for(b.T, 64, 520, 6, 2, oapl.OAPL_BF16, True, 0, max(lens))[1:] == (12288, 6)
+    res = _run(b, max_rollout_len=max(lens))
+    _check(b, res, ref, lp_tol=2e-2, rel_tol=1e-3, g_rtol=2e-2, g_atol_frac=6e-3)
+    res = _run(b)
+    _check(b, res, ref, lp_tol=2e-2, rel_tol=1e-3, g_rtol=2e-2, g_atol_frac=6e-3, fallback=True)
+    # a ring one buffer short of what the longest rollout needs falls back too
+    res = _run(b, max_rollout_len=4 * 12288)
     _check(b, res, ref, lp_tol=2e-2, rel_tol=1e-3, g_rtol=2e-2, g_atol_frac=6e-3, fallback=True)
 
 
@@ -171,19 +178,24 @@ def test_bf16_rollout_longer_than_a_panel_takes_two_passes():
     (384, [300, 380, 0, 200, 350, 90, 384, 1], False),    # 5 one-tile panels, rollouts straddle every boundary
     (768, [700, 33, 768, 500, 2, 640], False),            # 4 two-tile panels
     (384, [500, 300, 700, 200], True),                    # rollouts longer than the panel: two passes, same results
+    (384, [500, 300, 700, 200, 1], None),                 # ... unless the ring has buffers for them (3 here)
 ])
 def test_bf16_workspace_budget_sets_the_panel(cap, lens, fallback):
     """The workspace is the memory budget: handed one sized for panels of `cap` rows, the call works
     in panels of that size (several of them here, with rollouts straddling the boundaries) and gives
     the same results; a workspace one byte short of the smallest plan is refused."""
-    b = _custom_batch("bf16", d=128, V=1300, lens=lens, n_groups=2, seed=31, beta=0.8, noise=0.1)
-    nbytes, rows = oapl.workspace_bytes_for_panel(b.T, 128, 1300, len(lens), 2, oapl.OAPL_BF16, True, cap)
-    assert rows == cap and nbytes < oapl.workspace_bytes(b.T, 128, 1300, len(lens), 2, oapl.OAPL_BF16, True)
+    b = _custom_batch("bf16", d=128, V=1300, lens=lens, n_groups=2 if len(lens) % 2 == 0 else 1, seed=31, beta=0.8,
+                      noise=0.1)
+    ring = fallback is None
+    nbytes, rows, bufs = oapl.workspace_bytes_for(b.T, 128, 1300, len(lens), b.n_groups, oapl.OAPL_BF16, True, cap,
+                                                  max(lens) if ring else 0)
+    assert rows == cap and bufs == (1 + -(-max(lens) // cap) if ring else 2)
+    assert nbytes < oapl.workspace_bytes(b.T, 128, 1300, len(lens), b.n_groups, oapl.OAPL_BF16, True) or ring
     ws = torch.empty(nbytes, dtype=torch.uint8, device=DEV)
     res = _run(b, workspace=ws)
     ref = oracle_full(b)
-    _check(b, res, ref, lp_tol=2e-2, rel_tol=1e-3, g_rtol=2e-2, g_atol_frac=6e-3, fallback=fallback)
-    least = oapl.workspace_bytes_for_panel(b.T, 128, 1300, len(lens), 2, oapl.OAPL_BF16, True, 1)[0]
+    _check(b, res, ref, lp_tol=2e-2, rel_tol=1e-3, g_rtol=2e-2, g_atol_frac=6e-3, fallback=bool(fallback))
+    least = oapl.workspace_bytes_for(b.T, 128, 1300, len(lens), b.n_groups, oapl.OAPL_BF16, True, 1)[0]
     with pytest.raises(oapl.OaplError) as e:
         _run(b, workspace=torch.empty(least - 256, dtype=torch.uint8, device=DEV))
     assert e.value.status == 7
@@ -192,7 +204,7 @@ def test_bf16_workspace_budget_sets_the_panel(cap, lens, fallback):
 def test_f32_workspace_budget_sets_the_panel():
     lens = [0, 1, 37, 64, 0, 129, 5, 64]
     b = _custom_batch("f32", d=72, V=1000, lens=lens, n_groups=3, seed=1, beta=0.7)
-    nbytes, rows = oapl.workspace_bytes_for_panel(b.T, 72, 1000, len(lens), 3, oapl.OAPL_F32, True, 100)
+    nbytes, rows, _ = oapl.workspace_bytes_for(b.T, 72, 1000, len(lens), 3, oapl.OAPL_F32, True, 100)
     assert rows == 100
     res = _run(b, workspace=torch.empty(nbytes, dtype=torch.uint8, device=DEV))
     _check(b, res, oracle_full(b), lp_tol=1e-5, rel_tol=1e-5, g_rtol=1e-4, g_atol_frac=3e-6)
@@ -468,17 +480,25 @@ def test_empty_batch_and_forward_only():
 
 
 def test_peaked_logits_stay_finite():
-    """Hidden states scaled x30: logits of magnitude ~100, soft-max nearly one-hot."""
-    b = _custom_batch("bf16", d=128, V=1500, lens=[300], n_groups=1, seed=13, beta=1.0)
+    """Hidden states scaled x30: logits of magnitude ~100, soft-max nearly one-hot.  Two rollouts of
+    one prompt with different rewards and a drifted inference policy keep the residuals of order one
+    (a batch whose residuals are themselves rounding noise would only measure that noise), so the
+    stated bf16 tolerances apply unchanged."""
+    b = _custom_batch("bf16", d=128, V=1500, lens=[180, 120], n_groups=1, seed=13, beta=1.0)
     b.H = (b.H.float() * 30).bfloat16()
-    b.logq = synth.engine_logprobs(b.H, b.W, b.tokens)
+    b.rewards = torch.tensor([1.0, 0.0], device=DEV)
+    g = torch.Generator(device=DEV)
+    g.manual_seed(1313)
+    b.logq = (synth.engine_logprobs(b.H, b.W, b.tokens) + 0.1 * torch.randn(b.T, generator=g, device=DEV)).contiguous()
     res = _run(b)
     ref = oracle_full(b)
+    assert np.abs(ref["logprob"]).max() > 50 and np.abs(ref["delta"]).min() > 0.05     # peaked, and not a noise test
     lp = f64(res.logprob)
     assert np.all(np.isfinite(lp)) and np.all(lp <= 0)
-    assert np.abs(lp - ref["logprob"]).max() <= 2e-2 * np.maximum(1.0, np.abs(ref["logprob"]).max() / 100)
+    assert np.abs(lp - ref["logprob"]).max() <= 2e-2
+    assert rel(float(res.loss.item()), ref["loss"]) <= 1e-3
     assert np.isfinite(f64(res.dH)).all() and np.isfinite(f64(res.dW)).all()
-    assert rel(grad_norm(f64(res.dH), f64(res.dW)), grad_norm(ref["dH"], ref["dW"])) <= 5e-3
+    assert rel(grad_norm(f64(res.dH), f64(res.dW)), grad_norm(ref["dH"], ref["dW"])) <= 1e-3
 
 
 # ---------------------------------------------------------------- GRPO baseline (Sec. 2) --
