@@ -62,6 +62,10 @@ def parse():
     ap.add_argument("--panel-rows", type=int, default=0,
                     help="size the workspace for backward panels of at most this many token rows (0 = the "
                          "library's default); the library derives its panel from the workspace it is handed")
+    ap.add_argument("--hidden-scale", type=float, default=1.0,
+                    help="power probe, not a benchmark: multiply the hidden states by this before the run (0 = all-zero "
+                         "H: same kernels, shapes and launch configuration, operands that toggle few bits); the JSON "
+                         "line is marked and carries no baseline")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-tokens", type=int, default=2048)
     ap.add_argument("--calibration-copy", action="store_true",
@@ -121,6 +125,8 @@ def main():
     cfg = synth.CONFIGS[args.workload]
     batch = synth.make_batch(cfg, dev)
     T, d, V = batch.T, cfg.d, cfg.V
+    if args.hidden_scale != 1.0:
+        batch.H.mul_(args.hidden_scale)
     dt_code = oapl.OAPL_BF16 if cfg.dtype == "bf16" else oapl.OAPL_F32
     # the trainer knows its generation limit: panel buffers for the longest rollout of the workload
     longest = int((batch.seq_offsets[1:] - batch.seq_offsets[:-1]).max().item()) if batch.n_seq else 0
@@ -219,7 +225,9 @@ def main():
         "panel_buffers": panel_buffers if backward else None, "longest_rollout": longest,
         "kernels": kernels, "roofline": roofline, "loss" if args.path in ("loss", "grpo") else "output_checksum": loss,
     }
-    if not args.no_cpu_baseline and args.path == "loss":
+    if args.hidden_scale != 1.0:
+        out["power_probe"] = f"hidden states scaled by {args.hidden_scale}: not the benchmark workload"
+    if not args.no_cpu_baseline and args.path == "loss" and args.hidden_scale == 1.0:
         out["cpu_baseline"] = cpu_baseline(batch, args.cpu_sample_tokens)
     print(json.dumps(out))
 

@@ -345,37 +345,76 @@ __device__ __forceinline__ void store_tile_both_ways(lds_char_ptr smem, const f3
 // Half the registers of the fp32 tile, so nothing spills around the stores.
 // ---------------------------------------------------------------------------
 
+// 4 x 4 transpose of 16-byte pieces across the four lanes of a quad: lane q hands its piece c to
+// lane c and ends up holding, as piece r, what lane r held as piece q.  Two butterfly steps
+// (partner lane ^ 1, then lane ^ 2), each a select, a quad-permute DPP move and two selects per
+// exchanged piece.  All four lanes of the quad must be active.
+template <int CTRL, class V4>
+__device__ __forceinline__ V4 quad_xchg(const V4 v) {
+  V4 r;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    const auto x = v[e];   // a copy: a vector element is not an object whose bytes can be reinterpreted in place
+    r[e] = __builtin_bit_cast(decltype(x), __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), CTRL, 0xF, 0xF, true));
+  }
+  return r;
+}
+template <class V4>
+__device__ __forceinline__ void quad_transpose(V4 (&p)[4]) {
+  const bool b0 = (threadIdx.x & 1) != 0, b1 = (threadIdx.x & 2) != 0;
+#pragma unroll
+  for (int c = 0; c < 4; c += 2) {       // lane bit 0 <-> piece bit 0
+    const V4 r = quad_xchg<0xB1 /* quad_perm 1,0,3,2 */>(b0 ? p[c] : p[c + 1]);
+    p[c] = b0 ? r : p[c];
+    p[c + 1] = b0 ? p[c + 1] : r;
+  }
+#pragma unroll
+  for (int c = 0; c < 2; ++c) {          // lane bit 1 <-> piece bit 1
+    const V4 r = quad_xchg<0x4E /* quad_perm 2,3,0,1 */>(b1 ? p[c] : p[c + 2]);
+    p[c] = b1 ? r : p[c];
+    p[c + 2] = b1 ? p[c + 2] : r;
+  }
+}
+
 // Copy with rows = n, k = m, straight from registers.  A lane owns 4 consecutive m (8 bytes) of its
-// row n per (i, q) and the other lane half owns the 8 bytes next to them, so the 64 bytes of row n
-// that one MFMA block covers are spread over two lanes in 8-byte pieces.  The halves first trade
+// row n per (i, q) and the other lane half owns the 8 bytes next to them.  The halves first trade
 // registers (v_permlane32_swap: the lower half hands over its pieces q = 2, 3 and receives the
-// upper half's q = 0, 1), after which each lane holds 32 contiguous bytes and stores them as two
-// 16-byte words: half as many store instructions, twice the bytes per address.  Destroys pk.
-// `strip` is block (n-tile, 0) of the destination, kb0 the first k-block (m0 / 64).
+// upper half's q = 0, 1), after which each lane holds two 16-byte pieces per MFMA block row i, four
+// in all: with its other half, the whole 128-byte line of row n in this k-block.  Stored as they are,
+// every store instruction would scatter 16-byte pieces over 32 lines (measured: 25 bytes per write
+// request, about one request per clock and CU).  So the four lanes of a quad, which hold four
+// neighbouring rows, transpose their pieces first: lane q then holds piece q of each of the four
+// rows, and every store instruction writes whole lines, 8 lanes per line (+2.7 % on the sweep).
+// Destroys pk.  `strip` is block (n-tile, 0) of the destination, kb0 the first k-block (m0 / 64).
 template <class C>
 __device__ __forceinline__ void store_nm_packed_direct(uint32_t (&pk)[C::TM][C::TN][8], bf16_t* strip, int kb0) {
+  static_assert(C::TM == 2 && C::TM * 32 == kPackK, "a wave row spans exactly one packed k-block: 4 pieces of 16 bytes per lane");
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int wm = wave / C::WN, wn = wave % C::WN;
-  const int h = lane >> 5;
+  const int h = lane >> 5, q = lane & 3;
+  // piece q of a row sits at byte (q >> 1) * 64 + 32 h + 16 (q & 1) of its 128-byte line
+  char* base = (char*)strip + (int64_t)(kb0 + wm) * C::STAGE_B + (q >> 1) * 64 + 32 * h + 16 * (q & 1);
 #pragma unroll
   for (int j = 0; j < C::TN; ++j) {
-    const int n_l = wn * C::TN * 32 + j * 32 + (lane & 31);
+    u32x4 piece[4];
 #pragma unroll
     for (int i = 0; i < C::TM; ++i) {
-      const int m_blk = wm * C::TM * 32 + i * 32;              // multiple of 32: k-block m_blk / 64, half m_blk % 64
-      char* dst = (char*)strip + (int64_t)(kb0 + m_blk / kPackK) * C::STAGE_B + n_l * kPackRowBytes +
-                  (m_blk % kPackK) * 2 + 32 * h;
       uint32_t a[4], b[4];
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
-        // a: own word (lower lanes) / the lower half's word e + 4 (upper lanes);  b: the upper half's word e / own
         const auto r = __builtin_amdgcn_permlane32_swap(pk[i][j][e], pk[i][j][e + 4], false, false);
         a[e] = r[0];
         b[e] = r[1];
       }
-      *(u32x4*)(dst) = u32x4{a[0], a[1], b[0], b[1]};
-      *(u32x4*)(dst + 16) = u32x4{a[2], a[3], b[2], b[3]};
+      piece[2 * i] = u32x4{a[0], a[1], b[0], b[1]};
+      piece[2 * i + 1] = u32x4{a[2], a[3], b[2], b[3]};
     }
+    // the four lanes of a quad hold four neighbouring rows: after the transpose lane q holds piece q of
+    // each of them, and every store instruction writes whole 128-byte lines (8 lanes per line)
+    quad_transpose(piece);
+    const int n_q = wn * C::TN * 32 + j * 32 + (lane & 28);
+#pragma unroll
+    for (int r = 0; r < 4; ++r) *(u32x4*)(base + (n_q + r) * kPackRowBytes) = piece[r];
   }
 }
 
@@ -988,28 +1027,33 @@ k_bwd_dw(const bf16_t* __restrict__ HTp, const bf16_t* __restrict__ GTp, int t_n
 
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int wm = wave / C::WN, wn = wave % C::WN;
-  const int h = lane >> 5;
+  const int h = lane >> 5, q = lane & 3;
+  // A lane owns 4 pieces of 4 consecutive j (16 bytes) of its row v per MFMA block; the four lanes of a
+  // quad (four neighbouring rows) trade pieces so that lane q holds piece q of each of the four rows:
+  // every load and store of the read-add-write then covers whole 128-byte lines (8 lanes per line).
 #pragma unroll
   for (int j = 0; j < C::TN; ++j) {
-    const int n = n0 + wn * C::TN * 32 + j * 32 + (lane & 31);
-    if (n >= V) continue;
-    float* row = dW + (int64_t)n * d;
+    const int n_q = n0 + wn * C::TN * 32 + j * 32 + (lane & 28);
 #pragma unroll
-    for (int i = 0; i < C::TM; ++i)
+    for (int i = 0; i < C::TM; ++i) {
+      f32x4 piece[4];
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const int m = m0 + wm * C::TM * 32 + i * 32 + 8 * q + 4 * h;
-        if (m < d) {  // d is a multiple of 8, so the 4 lanes of a quad are in or out together
-          f32x4 v;
-          v[0] = acc[i][j][4 * q + 0];
-          v[1] = acc[i][j][4 * q + 1];
-          v[2] = acc[i][j][4 * q + 2];
-          v[3] = acc[i][j][4 * q + 3];
-          f32x4* p = (f32x4*)(row + m);
-          if (accumulate) v += *p;
-          *p = v;
+      for (int c = 0; c < 4; ++c)
+        piece[c] = f32x4{acc[i][j][4 * c + 0], acc[i][j][4 * c + 1], acc[i][j][4 * c + 2], acc[i][j][4 * c + 3]};
+      quad_transpose(piece);
+      const int m = m0 + wm * C::TM * 32 + i * 32 + 8 * q + 4 * h;
+      if (m < d) {  // d is a multiple of 8, so the lanes of a line are in or out together
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          if (n_q + r < V) {
+            f32x4* p = (f32x4*)(dW + (int64_t)(n_q + r) * d + m);
+            f32x4 v = piece[r];
+            if (accumulate) v += *p;
+            *p = v;
+          }
         }
       }
+    }
   }
 }
 
