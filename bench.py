@@ -115,7 +115,8 @@ def main():
               "(no collectives); run with --gpus 1", file=sys.stderr)
         sys.exit(2)
     import torch
-    from paper_2602_19362_amd import oapl, synth
+    from paper_2602_19362_amd import oapl
+    from workloads import synth
 
     if not torch.cuda.is_available():
         print("bench.py needs a GPU (there is no CPU fallback of the product path)", file=sys.stderr)

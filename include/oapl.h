@@ -107,8 +107,11 @@ size_t oapl_workspace_bytes(int64_t T, int32_t d, int32_t V, int32_t n_seq,
  *     keeps a ring of panels: 1 + ceil(longest rollout / panel rows) buffers
  *     serve rollouts of that length.  oapl_workspace_bytes sizes two buffers
  *     (rollouts up to one panel); pass max_rollout_len to size more (<= 0 =
- *     two).  Longer rollouts than the buffers serve are not an error: the call
- *     then takes the two-pass schedule (decided on the device).
+ *     two).  More than two buffers exist only at the library's own panel size
+ *     (a plan with smaller panels always has two: the loss call sees only a
+ *     byte count, and prefers larger panels to more buffers).  Longer rollouts
+ *     than the buffers serve are not an error: the call then takes the
+ *     two-pass schedule (decided on the device).
  * Returns the bytes needed, and the panel rows / buffers of that plan through
  * the host pointers (each may be NULL).  Returns 0 for invalid sizes.
  *

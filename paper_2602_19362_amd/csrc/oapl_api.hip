@@ -745,9 +745,13 @@ size_t oapl_workspace_bytes(int64_t T, int32_t d, int32_t V, int32_t n_seq, int3
 size_t oapl_workspace_bytes_for(int64_t T, int32_t d, int32_t V, int32_t n_seq, int32_t n_groups, int32_t dtype,
                                 int32_t with_backward, int64_t max_panel_rows, int64_t max_rollout_len,
                                 int64_t* panel_rows_out, int32_t* panel_buffers_out) {
-  Plan p;
+  Plan p, full;
   if (!make_plan(p, T, d, V, n_seq, n_groups, dtype, with_backward != 0, max_panel_rows)) return 0;
-  if (max_rollout_len > p.Tp && p.n_buf >= 2) {   // buffers for the longest rollout: 1 + ceil(len / panel)
+  if (!make_plan(full, T, d, V, n_seq, n_groups, dtype, with_backward != 0)) return 0;
+  // Buffers for the longest rollout, 1 + ceil(len / panel): only at the library's own panel size.  A
+  // loss call derives its plan from the byte count alone, and k buffers of a smaller panel could not
+  // be told from two buffers of a panel k / 2 times as large (which it prefers: larger panels are faster).
+  if (max_rollout_len > p.Tp && p.n_buf >= 2 && p.Tp == full.Tp) {
     const int64_t want = 1 + (max_rollout_len + p.Tp - 1) / p.Tp;
     Plan q;
     if (!make_plan(q, T, d, V, n_seq, n_groups, dtype, with_backward != 0, p.Tp, want, p.Tp)) return 0;

@@ -85,6 +85,7 @@ def test_workspace_is_the_memory_budget():
     assert wbf(*args, 0, 10 ** 9)[2] == 12                          # ceil(140897 / 12288) panels in all
     a3, _, _ = wbf(*args, 0, 12289)
     assert 0.98 * 12288 * per_row < a3 - full < 1.02 * 12288 * per_row
+    assert wbf(*args, 6144, 32768)[1:] == (6144, 2)                 # smaller panels: always two buffers
     # one panel is enough when the batch fits it
     assert wbf(6000, 4096, 151936, 8, 1, oapl.OAPL_BF16, True, 0, 50000)[1:] == (6144, 1)
     # d = 5120: 20 row tiles of dH per token tile; the plan picks a panel that fills whole rounds of 256 workgroups

@@ -32,7 +32,8 @@ import pytest
 import torch
 
 from oracle import oapl_oracle as orc
-from paper_2602_19362_amd import oapl, synth
+from paper_2602_19362_amd import oapl
+from workloads import synth
 from tests._util import f64, grad_norm, rel
 
 pytestmark = pytest.mark.gpu

@@ -13,7 +13,8 @@ import numpy as np
 import pytest
 import torch
 
-from paper_2602_19362_amd import oapl, synth
+from paper_2602_19362_amd import oapl
+from workloads import synth
 from tests._util import f64, grad_norm, oracle_full, rel
 
 pytestmark = pytest.mark.gpu
@@ -178,19 +179,17 @@ def test_bf16_default_panels_with_a_ring_of_buffers_for_long_rollouts():
     (384, [300, 380, 0, 200, 350, 90, 384, 1], False),    # 5 one-tile panels, rollouts straddle every boundary
     (768, [700, 33, 768, 500, 2, 640], False),            # 4 two-tile panels
     (384, [500, 300, 700, 200], True),                    # rollouts longer than the panel: two passes, same results
-    (384, [500, 300, 700, 200, 1], None),                 # ... unless the ring has buffers for them (3 here)
 ])
 def test_bf16_workspace_budget_sets_the_panel(cap, lens, fallback):
     """The workspace is the memory budget: handed one sized for panels of `cap` rows, the call works
     in panels of that size (several of them here, with rollouts straddling the boundaries) and gives
     the same results; a workspace one byte short of the smallest plan is refused."""
-    b = _custom_batch("bf16", d=128, V=1300, lens=lens, n_groups=2 if len(lens) % 2 == 0 else 1, seed=31, beta=0.8,
-                      noise=0.1)
-    ring = fallback is None
+    b = _custom_batch("bf16", d=128, V=1300, lens=lens, n_groups=2, seed=31, beta=0.8, noise=0.1)
+    # panels smaller than the library's own always come with two buffers, whatever the rollout length
     nbytes, rows, bufs = oapl.workspace_bytes_for(b.T, 128, 1300, len(lens), b.n_groups, oapl.OAPL_BF16, True, cap,
-                                                  max(lens) if ring else 0)
-    assert rows == cap and bufs == (1 + -(-max(lens) // cap) if ring else 2)
-    assert nbytes < oapl.workspace_bytes(b.T, 128, 1300, len(lens), b.n_groups, oapl.OAPL_BF16, True) or ring
+                                                  max(lens))
+    assert rows == cap and bufs == 2
+    assert nbytes < oapl.workspace_bytes(b.T, 128, 1300, len(lens), b.n_groups, oapl.OAPL_BF16, True)
     ws = torch.empty(nbytes, dtype=torch.uint8, device=DEV)
     res = _run(b, workspace=ws)
     ref = oracle_full(b)

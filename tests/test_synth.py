@@ -2,7 +2,7 @@
 import numpy as np
 import torch
 
-from paper_2602_19362_amd import synth
+from workloads import synth
 
 
 def test_tiny_config_shapes_and_determinism():

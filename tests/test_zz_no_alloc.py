@@ -5,7 +5,8 @@ import numpy as np
 import pytest
 import torch
 
-from paper_2602_19362_amd import oapl, synth
+from paper_2602_19362_amd import oapl
+from workloads import synth
 
 pytestmark = pytest.mark.gpu
 

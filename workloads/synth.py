@@ -7,8 +7,10 @@ datasets nor its checkpoints are used here: every batch below is drawn from a
 seeded generator and only reproduces the *shapes* (hidden size, vocabulary,
 group structure, length mix) and the value distributions of such a batch.
 
-This module only produces inputs.  It computes nothing of the OAPL objective.
-The one piece of arithmetic it holds is a stand-in for the *inference engine*:
+This module only produces inputs and is not part of the library (it lives
+beside the tests and the benchmark that use it).  It computes nothing of the
+OAPL objective.  The one piece of arithmetic it holds is a stand-in for the
+*inference engine*:
 the lagged policy's log-probabilities of the sampled tokens are an input of
 the method (Sec. 3.1, Eq. 3 uses them as given), and in the paper's system they
 come from a separate engine with its own numerics.  Here they come from plain
