@@ -465,14 +465,17 @@ __device__ __forceinline__ void store_mn_pk_packed(lds_char_ptr smem, bf16_t* ba
 // The kernels use SN = 4: an 8 x 4 patch of 256 x 384 tiles needs 8 x 32 KB +
 // 4 x 48 KB of operands per k-step, the least for 32 tiles (measured +1.5 %
 // over 4 x 8, and 8 % over 2 x 16).
-template <int SN>
-__device__ __forceinline__ void strip_tile(int L, int MT, int NTl, int& mt, int& nt) {
+__device__ __forceinline__ void strip_tile(const int SN, int L, int MT, int NTl, int& mt, int& nt) {
   const int per_strip = SN * MT;
   const int strip = L / per_strip;
   const int rem = L - strip * per_strip;
   const int width = (NTl - strip * SN) < SN ? (NTl - strip * SN) : SN;
   mt = rem / width;
   nt = strip * SN + rem % width;
+}
+template <int SN>
+__device__ __forceinline__ void strip_tile(int L, int MT, int NTl, int& mt, int& nt) {
+  strip_tile(SN, L, MT, NTl, mt, nt);
 }
 
 // ---------------------------------------------------------------------------
@@ -491,7 +494,7 @@ __device__ __forceinline__ void strip_tile(int L, int MT, int NTl, int& mt, int&
 template <class C, bool ENT>
 __global__ void __launch_bounds__(C::NT)
 k_fwd_lse(const bf16_t* __restrict__ Wp, const bf16_t* __restrict__ Hp, int V, int64_t T, int n_kt,
-          int n_splits, float2* __restrict__ partials, float* __restrict__ upart, Gate gate) {
+          int n_splits, int patch_tiles, float2* __restrict__ partials, float* __restrict__ upart, Gate gate) {
   extern __shared__ __attribute__((aligned(1024))) char smem_raw[];
   lds_char_ptr smem = (lds_char_ptr)smem_raw;
   if (gate_closed(gate)) return;
@@ -500,7 +503,14 @@ k_fwd_lse(const bf16_t* __restrict__ Wp, const bf16_t* __restrict__ Hp, int V, i
   const int total = n_tiles * n_splits;
   const int L = xcd_logical_id(blockIdx.x, total);
   if (L >= total) return;
-  const int nt = L / n_splits, split = L % n_splits;
+  // Consecutive logical ids walk `patch_tiles` token tiles first, then the vocabulary splits: the ~32
+  // workgroups resident on one XCD are then patch_tiles token tiles x 32 / patch_tiles splits, which
+  // walk their splits in step and share each W block patch_tiles ways (each H block is shared by the
+  // splits of its token tile).  patch_tiles = 1 keeps one token tile's H strip to an XCD: every XCD
+  // then streams all of W once per token tile, which is the better trade only while several H strips
+  // would not fit its L2 (chosen on the host from the strip size).
+  int split, nt;
+  strip_tile(patch_tiles, L, n_splits, n_tiles, split, nt);
   const int MT = (V + C::BM - 1) / C::BM;
   const int mt_begin = (int)((int64_t)split * MT / n_splits);
   const int mt_end = (int)((int64_t)(split + 1) * MT / n_splits);

@@ -303,14 +303,17 @@ static int forward_scores(const Plan& p, const void* H, const void* W, const int
     const bf16_t* Hp = (const bf16_t*)(ws + p.off_Hp);
     const int64_t n_tiles = (T + Cfg::BN - 1) / Cfg::BN;
     const int64_t total = n_tiles * p.n_parts;
+    // token tiles per XCD patch: four while a token tile's packed H strip is at most 2 MiB (d <= 2730:
+    // +4 % measured at d = 2048), one beyond that (four strips of 3 MiB thrash the 4 MiB L2: -5 % at d = 4096)
+    const int patch_tiles = (size_t)p.n_kt_d * kPackBlockBytesB <= ((size_t)2 << 20) ? 4 : 1;
     {
       ScopedKernelTimer tm(kFwdLse, st, timed);
       if (entropy_out)
         k_fwd_lse<Cfg, true><<<(unsigned)round_up(total, 8), Cfg::NT, Cfg::LDS_BYTES, st>>>(
-            Wp, Hp, p.V, T, p.n_kt_d, p.n_parts, partials, upart, gate);
+            Wp, Hp, p.V, T, p.n_kt_d, p.n_parts, patch_tiles, partials, upart, gate);
       else
         k_fwd_lse<Cfg, false><<<(unsigned)round_up(total, 8), Cfg::NT, Cfg::LDS_BYTES, st>>>(
-            Wp, Hp, p.V, T, p.n_kt_d, p.n_parts, partials, nullptr, gate);
+            Wp, Hp, p.V, T, p.n_kt_d, p.n_parts, patch_tiles, partials, nullptr, gate);
     }
     OAPL_LAUNCH_CHECK();
     k_lse_finish<true><<<grid1d(T, 256), 256, 0, st>>>(partials, p.n_parts, T, zy, logq, logprob_out, lse_out, lse2,
@@ -458,7 +461,7 @@ static int sweep_path(const Plan& p, const void* H, const void* W, const int32_t
   OAPL_LAUNCH_CHECK();
   // reference exponents: running maximum over the first vocabulary tile, one workgroup per token tile
   k_fwd_lse<Cfg, false><<<(unsigned)round_up(n_tiles, 8), Cfg::NT, Cfg::LDS_BYTES, st>>>(
-      Wp, Hp, V < Cfg::BM ? V : Cfg::BM, T, p.n_kt_d, 1, sample, nullptr, fast);
+      Wp, Hp, V < Cfg::BM ? V : Cfg::BM, T, p.n_kt_d, 1, 1, sample, nullptr, fast);
   OAPL_LAUNCH_CHECK();
   k_sweep_ref<<<grid1d(T, 256), 256, 0, st>>>(sample, zy, T, ref2);
   OAPL_LAUNCH_CHECK();
