@@ -1001,6 +1001,45 @@ k_bwd_dh(const bf16_t* __restrict__ WTp, int wt_n_kt, const bf16_t* __restrict__
   }
 }
 
+// fp32 tile -> dW[n][m] (row pitch d), overwritten or added to, straight from the accumulators.
+// A lane owns 4 pieces of 4 consecutive m (16 bytes) of its row n per MFMA block; the four lanes of a
+// quad (four neighbouring rows) trade pieces so that lane q holds piece q of each of the four rows:
+// every load and store then covers whole 128-byte lines (8 lanes per line).  The four old values of
+// an MFMA block are requested together, from clamped (always valid) addresses, before the transpose,
+// so the read-add-write waits for memory once per block, not once per piece (eight at once spill).
+template <class C, bool ACCUMULATE>
+__device__ __forceinline__ void store_dw_tile(const f32x16 (&acc)[C::TM][C::TN], float* __restrict__ dW, int d, int V,
+                                              int m0, int n0) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int wm = wave / C::WN, wn = wave % C::WN;
+  const int h = lane >> 5, q = lane & 3;
+#pragma unroll
+  for (int j = 0; j < C::TN; ++j) {
+    const int n_q = n0 + wn * C::TN * 32 + j * 32 + (lane & 28);
+#pragma unroll
+    for (int i = 0; i < C::TM; ++i) {
+      f32x4 piece[4], old[4];
+      const int m = m0 + wm * C::TM * 32 + i * 32 + 8 * q + 4 * h;
+      if (ACCUMULATE) {
+        const int mc = m < d ? m : d - 4;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const int nc = n_q + r < V ? n_q + r : V - 1;
+          old[r] = *(const f32x4*)(dW + (int64_t)nc * d + mc);
+        }
+      }
+#pragma unroll
+      for (int c = 0; c < 4; ++c)
+        piece[c] = f32x4{acc[i][j][4 * c + 0], acc[i][j][4 * c + 1], acc[i][j][4 * c + 2], acc[i][j][4 * c + 3]};
+      quad_transpose(piece);
+#pragma unroll
+      for (int r = 0; r < 4; ++r)
+        if (m < d && n_q + r < V)
+          *(f32x4*)(dW + (int64_t)(n_q + r) * d + m) = ACCUMULATE ? piece[r] + old[r] : piece[r];
+    }
+  }
+}
+
 // ---------------------------------------------------------------------------
 // Backward, step 3: dW[v][j] (+)= sum_t G[t][v] * (f_t H[t][j])
 //   A = packed (diag(f) H)^T (rows = hidden index j, k = panel tokens), B = GTp (rows = vocabulary).
@@ -1035,36 +1074,8 @@ k_bwd_dw(const bf16_t* __restrict__ HTp, const bf16_t* __restrict__ GTp, int t_n
   ml.start(smem);
   ml.finish(smem, nk, acc);
 
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int wm = wave / C::WN, wn = wave % C::WN;
-  const int h = lane >> 5, q = lane & 3;
-  // A lane owns 4 pieces of 4 consecutive j (16 bytes) of its row v per MFMA block; the four lanes of a
-  // quad (four neighbouring rows) trade pieces so that lane q holds piece q of each of the four rows:
-  // every load and store of the read-add-write then covers whole 128-byte lines (8 lanes per line).
-#pragma unroll
-  for (int j = 0; j < C::TN; ++j) {
-    const int n_q = n0 + wn * C::TN * 32 + j * 32 + (lane & 28);
-#pragma unroll
-    for (int i = 0; i < C::TM; ++i) {
-      f32x4 piece[4];
-#pragma unroll
-      for (int c = 0; c < 4; ++c)
-        piece[c] = f32x4{acc[i][j][4 * c + 0], acc[i][j][4 * c + 1], acc[i][j][4 * c + 2], acc[i][j][4 * c + 3]};
-      quad_transpose(piece);
-      const int m = m0 + wm * C::TM * 32 + i * 32 + 8 * q + 4 * h;
-      if (m < d) {  // d is a multiple of 8, so the lanes of a line are in or out together
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-          if (n_q + r < V) {
-            f32x4* p = (f32x4*)(dW + (int64_t)(n_q + r) * d + m);
-            f32x4 v = piece[r];
-            if (accumulate) v += *p;
-            *p = v;
-          }
-        }
-      }
-    }
-  }
+  if (accumulate) store_dw_tile<C, true>(acc, dW, d, V, m0, n0);
+  else store_dw_tile<C, false>(acc, dW, d, V, m0, n0);
 }
 
 // ---------------------------------------------------------------------------
