@@ -30,11 +30,11 @@ PEAK_BF16_TFLOPS = 2516.6     # MI355X dense bf16 MFMA: 256 CU x 4096 flop/clk x
 # sources at run time and the figure is reported as null when they differ.
 TRAFFIC = {
     "workload": "qwen7b",
-    "sources_sha256_16": "05c4fd4f4b82386c",
-    "per_launch_bytes": {          # averages over the step's three panels (61440, 61440, 18017 rows)
-        "k_sweep": {"read": 70.76e9, "write": 28.69e9},
-        "k_bwd_dh": {"read": 68.55e9, "write": 0.38e9},
-        "k_bwd_dw": {"read": 79.50e9, "write": 2.49e9},
+    "sources_sha256_16": "e721e6fa9f9613dc",
+    "per_launch_bytes": {          # averages over the step's 12 panels (11 of 12288 rows, one of 5729)
+        "k_sweep": {"read": 17.80e9, "write": 7.28e9},
+        "k_bwd_dh": {"read": 16.85e9, "write": 0.10e9},
+        "k_bwd_dw": {"read": 19.06e9, "write": 2.49e9},
     },
 }
 

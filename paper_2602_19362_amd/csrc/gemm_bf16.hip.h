@@ -381,8 +381,8 @@ __device__ __forceinline__ void quad_transpose(V4 (&p)[4]) {
 // registers (v_permlane32_swap: the lower half hands over its pieces q = 2, 3 and receives the
 // upper half's q = 0, 1), after which each lane holds two 16-byte pieces per MFMA block row i, four
 // in all: with its other half, the whole 128-byte line of row n in this k-block.  Stored as they are,
-// every store instruction would scatter 16-byte pieces over 32 lines (measured: 25 bytes per write
-// request, about one request per clock and CU).  So the four lanes of a quad, which hold four
+// every store instruction would scatter 16-byte pieces over 32 lines (measured: 43 bytes per write
+// request over the kernel, where a request can carry 64).  So the four lanes of a quad, which hold four
 // neighbouring rows, transpose their pieces first: lane q then holds piece q of each of the four
 // rows, and every store instruction writes whole lines, 8 lanes per line (+2.7 % on the sweep).
 // Destroys pk.  `strip` is block (n-tile, 0) of the destination, kb0 the first k-block (m0 / 64).
