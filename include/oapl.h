@@ -204,8 +204,7 @@ int32_t oapl_sample_tokens(const void* H, const void* W, int64_t T, int32_t d, i
  * call recomputes everything in two passes (log-sum-exp first, then soft-max
  * recompute per panel), in stream order, with no host involvement.  The
  * results of the two schedules agree to rounding.  fp32 and batches of fewer
- * than 64 tokens always run two passes (the sweep rounds the sampled token's
- * gradient entry to bf16, which only averages out over a batch).
+ * than 64 tokens always run two passes (nothing is gained by a sweep there).
  *
  * The same beta is used in Eq. 2 and Eq. 3, as the method section writes
  * them.  loss_scale = 1 gives the paper's plain sum; it exists so a caller can

@@ -57,9 +57,8 @@ struct Plan {
 };
 
 constexpr int kFlagWord = 8;   // status word that selects the two-pass path on the device
-// The single sweep rounds the sampled token's gradient entry to bf16 (2^-9 relative, a common factor of
-// that token's whole gradient row); over a batch these roundings average out, for a handful of tokens
-// they show in the gradient norm.  Smaller batches take the two-pass path, whose one-hot entry is exact.
+// A call this small gains nothing from the sweep's saved pass; it takes the two-pass path, whose one-hot
+// gradient entry is exact rather than exact up to the row-factor correction.
 constexpr int64_t kSweepMinTokens = 64;
 
 // Largest panel the plan may use: `max_panel_rows` <= 0 or above the library's size means that

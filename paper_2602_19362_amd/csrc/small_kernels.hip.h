@@ -404,7 +404,8 @@ k_sweep_ref(const float2* __restrict__ sample, const float* __restrict__ zy, int
 
 // Finishes one panel of the single sweep.  Per token row (panel-local index n, global t0 + n):
 //   S = sum of the vocabulary-tile partial sums (double, tile order),  lse = (ref2 + log2 S) ln 2,
-//   logprob = min(z_y - lse, 0),  diff = logprob - logq,  nis = -1 / S  (row factor of the gradient),
+//   logprob = min(z_y - lse, 0),  diff = logprob - logq,  nis = -1 / S  (row factor of the gradient, times the
+//   correction below),
 // and patches the sampled token's entry of the unnormalised soft-max panel, in both packed
 // copies, to  Pt[y] - S = -S (1 - p_y)  (computed from expm1 so it is accurate when p_y -> 1).
 // Rows whose sum left the accepted range raise the fallback flag.
@@ -425,10 +426,16 @@ k_sweep_finish(const float* __restrict__ spart, int n_vt, int64_t ld_s, int64_t 
   if (lp > 0.0) lp = 0.0;
   if (logprob_out) logprob_out[n] = (float)lp;
   diff[n] = lp - (double)logq[n];
-  nis[n] = (float)(-1.0 / S);
+  double row_factor = -1.0 / S;
   const int y = tokens[n];
   if (y >= 0 && y < V) {
-    const bf16_t patch = (bf16_t)(float)(S * expm1(lp));       // -S (1 - p_y)
+    const double entry = S * expm1(lp);                        // -S (1 - p_y)
+    const bf16_t patch = (bf16_t)(float)entry;
+    // The sampled token's entry carries nearly all of the row's gradient, and bf16 keeps 8 bits of it.
+    // The row factor absorbs that rounding: factor * patch is then the exact entry, and the relative
+    // error (<= 2^-8) moves to the row's other entries, whose joint weight in the gradient is small.
+    const double kept = (double)(float)patch;
+    if (kept != 0.0 && isfinite(entry)) row_factor *= entry / kept;
     // both copies are n-side operands: blocks of kPackRowsB rows x 64 k
     const int64_t blk = (int64_t)kPackRowsB * kPackK;             // elements of a packed block
     const int64_t nb = n / kPackRowsB, nr = n - nb * kPackRowsB;  // token row block / row inside it
@@ -436,6 +443,7 @@ k_sweep_finish(const float* __restrict__ spart, int n_vt, int64_t ld_s, int64_t 
     Gp[(nb * g_n_kt + (y >> 6)) * blk + nr * kPackK + (y & 63)] = patch;
     GTp[((int64_t)yb * gt_n_kt + (n >> 6)) * blk + (int64_t)yr * kPackK + (n & 63)] = patch;
   }
+  nis[n] = (float)row_factor;
 }
 
 }  // namespace oapl

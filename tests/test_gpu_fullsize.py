@@ -268,9 +268,10 @@ def test_full_size_configuration(name):
                    f"row-norm rel err max={np.max(np.abs(np.linalg.norm(w_gpu, axis=1) / np.linalg.norm(w_ref, axis=1) - 1)):.3e}")
         assert np.all(w_err <= bound), float(w_err.max())
         # The row of a token that was sampled once or twice is essentially c_t (1 - p_y) H_t of that one
-        # token, and the soft-max panel holds its entry rounded to bf16 (8 significant bits): up to 2^-8
-        # of the row's norm, independent from row to row (the batch's gradient norm does not see it).
-        assert np.all(np.abs(np.linalg.norm(w_gpu, axis=1) / np.linalg.norm(w_ref, axis=1) - 1) <= 2.0 ** -8 + 5e-4)
+        # token.  The soft-max panel holds that entry in bf16 (up to 2^-8 off), and the row factor is
+        # corrected for exactly that rounding, so the row's norm must agree far better than 2^-8 = 3.9e-3;
+        # what remains is the error of c_t itself (the residual of a rollout of up to 32768 tokens).
+        assert np.all(np.abs(np.linalg.norm(w_gpu, axis=1) / np.linalg.norm(w_ref, axis=1) - 1) <= 2e-3)
 
         assert bool(torch.isfinite(res.dW).all()) and bool(torch.isfinite(res.dH.float()).all())
         col = res.dW.double().sum(0)

@@ -175,6 +175,29 @@ def test_bf16_default_panels_with_a_ring_of_buffers_for_long_rollouts():
     _check(b, res, ref, lp_tol=2e-2, rel_tol=1e-3, g_rtol=2e-2, g_atol_frac=6e-3, fallback=True)
 
 
+@pytest.mark.parametrize("longest,buffers_sized_for,fallback", [
+    (24576, 24576, False),      # exactly two panels long: three buffers serve it
+    (24577, 24576, True),       # one token more than the three buffers serve: two passes
+    (24577, 24577, False),      # ... four buffers: single sweep again
+])
+def test_bf16_ring_of_panel_buffers_at_its_limit(longest, buffers_sized_for, fallback):
+    """A rollout of exactly (buffers - 1) panels is the longest the single sweep serves; it starts in the
+    middle of a panel here, so it straddles three (four) of them.  OAPL and the GRPO baseline."""
+    lens = [5000, longest, 1, 0, 9000, 12288]
+    b = _custom_batch("bf16", d=64, V=520, lens=lens, n_groups=2, seed=6, beta=1.0, noise=0.02)
+    nbytes, rows, bufs = oapl.workspace_bytes_for(b.T, 64, 520, len(lens), 2, oapl.OAPL_BF16, True, 0, buffers_sized_for)
+    assert rows == 12288 and bufs == 1 + -(-buffers_sized_for // 12288)
+    ws = torch.empty(nbytes, dtype=torch.uint8, device=DEV)
+    res = _run(b, workspace=ws)
+    _check(b, res, oracle_full(b), lp_tol=2e-2, rel_tol=1e-3, g_rtol=2e-2, g_atol_frac=6e-3, fallback=fallback)
+    b.rewards = torch.tensor([1, 0, 0, 1, 1, 0], dtype=torch.float32, device=DEV)
+    logq, logp_old = _grpo_inputs(b, 6)
+    gres = _grpo(b.H, b.W, b.tokens, logq, logp_old, b.seq_offsets, b.rewards, b.group_ids, 2, workspace=ws)
+    torch.cuda.synchronize()
+    assert oapl.took_two_passes(ws) == (fallback and _MODE[0] == "single_sweep")
+    _grpo_check(b, logq, logp_old, gres, lp_tol=2e-2, rel_tol=1e-3, g_rtol=2e-2, g_atol_frac=6e-3)
+
+
 @pytest.mark.parametrize("cap,lens,fallback", [
     (384, [300, 380, 0, 200, 350, 90, 384, 1], False),    # 5 one-tile panels, rollouts straddle every boundary
     (768, [700, 33, 768, 500, 2, 640], False),            # 4 two-tile panels
