@@ -30,11 +30,11 @@ PEAK_BF16_TFLOPS = 2516.6     # MI355X dense bf16 MFMA: 256 CU x 4096 flop/clk x
 # sources at run time and the figure is reported as null when they differ.
 TRAFFIC = {
     "workload": "qwen7b",
-    "sources_sha256_16": "e721e6fa9f9613dc",
+    "sources_sha256_16": "710b1527f0ae51ae",
     "per_launch_bytes": {          # averages over the step's 12 panels (11 of 12288 rows, one of 5729)
-        "k_sweep": {"read": 17.80e9, "write": 7.28e9},
-        "k_bwd_dh": {"read": 16.85e9, "write": 0.10e9},
-        "k_bwd_dw": {"read": 19.06e9, "write": 2.49e9},
+        "k_sweep": {"read": 18.24e9, "write": 7.28e9},
+        "k_bwd_dh": {"read": 16.83e9, "write": 0.10e9},
+        "k_bwd_dw": {"read": 19.13e9, "write": 2.49e9},
     },
 }
 
@@ -66,6 +66,10 @@ def parse():
                     help="power probe, not a benchmark: multiply the hidden states by this before the run (0 = all-zero "
                          "H: same kernels, shapes and launch configuration, operands that toggle few bits); the JSON "
                          "line is marked and carries no baseline")
+    ap.add_argument("--library-gemm-context", action="store_true",
+                    help="context, not a benchmark: time the vendor library's bf16 GEMM (torch.matmul) on the three "
+                         "contractions of one backward panel of the workload (scores, dH, dW; same H, W and a soft-max "
+                         "panel computed from them), then exit; honours --hidden-scale")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-tokens", type=int, default=2048)
     ap.add_argument("--calibration-copy", action="store_true",
@@ -108,6 +112,40 @@ def cpu_baseline(batch, n_tokens):
     }
 
 
+def library_gemm_context(torch, batch, cfg, args):
+    """What the vendor library reaches on the same operands and shapes: the three dense contractions of
+    one 12288-row panel as plain GEMMs (bf16 in, bf16 out, no soft-max, no accumulation into dW).  Says how
+    much of the distance to the MFMA peak belongs to the chip (clock under load, operand delivery) rather
+    than to the kernels here; it is not part of the measured path."""
+    Tp = min(12288, batch.T)
+    H, W = batch.H[:Tp].contiguous(), batch.W
+    Z = torch.matmul(H, W.t())
+    G = torch.softmax(Z.float(), dim=1)
+    G[torch.arange(Tp, device=H.device), batch.tokens[:Tp].long()] -= 1.0
+    G = G.to(torch.bfloat16)
+    dH = torch.empty_like(H)
+    dW = torch.empty_like(W)
+    flop = 2.0 * Tp * cfg.V * cfg.d
+    rows = []
+    for name, fn in (("scores = H W^T", lambda: torch.matmul(H, W.t(), out=Z)),
+                     ("dH = G W", lambda: torch.matmul(G, W, out=dH)),
+                     ("dW = G^T H", lambda: torch.matmul(G.t(), H, out=dW))):
+        for _ in range(3):
+            fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(args.steps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / args.steps
+        rows.append({"gemm": name, "ms": round(ms, 3), "tflops": round(flop / ms / 1e9, 1),
+                     "frac_of_bf16_peak": round(flop / ms / 1e9 / PEAK_BF16_TFLOPS, 4)})
+    print(json.dumps({"context": "library_gemm", "workload": args.workload, "panel_rows": Tp, "d": cfg.d, "V": cfg.V,
+                      "hidden_scale": args.hidden_scale, "launches_timed": args.steps, "gemms": rows}))
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -128,6 +166,9 @@ def main():
     T, d, V = batch.T, cfg.d, cfg.V
     if args.hidden_scale != 1.0:
         batch.H.mul_(args.hidden_scale)
+    if args.library_gemm_context:
+        library_gemm_context(torch, batch, cfg, args)
+        return
     dt_code = oapl.OAPL_BF16 if cfg.dtype == "bf16" else oapl.OAPL_F32
     # the trainer knows its generation limit: panel buffers for the longest rollout of the workload
     longest = int((batch.seq_offsets[1:] - batch.seq_offsets[:-1]).max().item()) if batch.n_seq else 0
