@@ -29,6 +29,13 @@
 //     needs no cross-lane traffic until the very end;
 //   * outputs with m contiguous (G[t][v], dH[t][j], dW[v][j]) get 4
 //     consecutive m per lane.
+//
+// The bodies of the tile kernels are compiled in the device pass only (__HIP_DEVICE_COMPILE__).
+// They use instructions that gfx950 alone has (16-byte direct-to-LDS loads, the 32x32x16 bf16
+// MFMA, v_permlane32_swap).  The host pass needs nothing but the signatures, for its launch stubs;
+// it checks builtins against a generic target, keeps its complaints about device code to itself,
+// and has been seen to drop a kernel's launch stub, or to refuse a launch as "no matching
+// function", after an unrelated edit of the main loop.
 #pragma once
 
 #include "common.hip.h"
@@ -495,6 +502,7 @@ template <class C, bool ENT>
 __global__ void __launch_bounds__(C::NT)
 k_fwd_lse(const bf16_t* __restrict__ Wp, const bf16_t* __restrict__ Hp, int V, int64_t T, int n_kt,
           int n_splits, int patch_tiles, float2* __restrict__ partials, float* __restrict__ upart, Gate gate) {
+#if defined(__HIP_DEVICE_COMPILE__)
   extern __shared__ __attribute__((aligned(1024))) char smem_raw[];
   lds_char_ptr smem = (lds_char_ptr)smem_raw;
   if (gate_closed(gate)) return;
@@ -618,6 +626,7 @@ k_fwd_lse(const bf16_t* __restrict__ Wp, const bf16_t* __restrict__ Hp, int V, i
       if (ENT) upart[(int64_t)split * T + n0 + n_l] = ua;
     }
   }
+#endif
 }
 
 // ---------------------------------------------------------------------------
@@ -635,6 +644,7 @@ template <class C>
 __global__ void __launch_bounds__(C::NT)
 k_fwd_sample(const bf16_t* __restrict__ Wp, const bf16_t* __restrict__ Hp, int V, int64_t T, int n_kt, int n_splits,
              float inv_temperature, uint32_t seed_lo, uint32_t seed_hi, float2* __restrict__ partials) {
+#if defined(__HIP_DEVICE_COMPILE__)
   extern __shared__ __attribute__((aligned(1024))) char smem_raw[];
   lds_char_ptr smem = (lds_char_ptr)smem_raw;
 
@@ -722,6 +732,7 @@ k_fwd_sample(const bf16_t* __restrict__ Wp, const bf16_t* __restrict__ Hp, int V
       partials[(int64_t)split * T + n0 + n_l] = make_float2(a.x, a.y);
     }
   }
+#endif
 }
 
 // ---------------------------------------------------------------------------
@@ -744,6 +755,7 @@ __global__ void __launch_bounds__(C::NT)
 k_bwd_dz(const bf16_t* __restrict__ Wp, const bf16_t* __restrict__ Hp_panel, int V, int64_t n_valid, int n_kt,
          const int32_t* __restrict__ tokens, const float* __restrict__ lse2, const float* __restrict__ inv_omp,
          bf16_t* __restrict__ Gp, int g_n_kt, bf16_t* __restrict__ GTp, int gt_n_kt, Gate gate) {
+#if defined(__HIP_DEVICE_COMPILE__)
   extern __shared__ __attribute__((aligned(1024))) char smem_raw[];
   lds_char_ptr smem = (lds_char_ptr)smem_raw;
   if (gate_closed(gate)) return;
@@ -822,6 +834,7 @@ k_bwd_dz(const bf16_t* __restrict__ Wp, const bf16_t* __restrict__ Hp_panel, int
 
   // Gp: rows = tokens (n), k = vocabulary (m);  GTp: rows = vocabulary (m), k = tokens (n)
   store_tile_both_ways<C>(smem, acc, Gp + (int64_t)nt * g_n_kt * (C::STAGE_B / 2), m0, GTp, gt_n_kt, n0);
+#endif
 }
 
 // ---------------------------------------------------------------------------
@@ -847,6 +860,7 @@ k_sweep(const bf16_t* __restrict__ Wp, const bf16_t* __restrict__ Hp_panel, int 
         const float* __restrict__ ref2 /* panel-local */, bf16_t* __restrict__ Gp, int g_n_kt,
         bf16_t* __restrict__ GTp, int gt_n_kt, float* __restrict__ spart /* [MT][ld_s], panel-local */,
         int64_t ld_s, Gate gate) {
+#if defined(__HIP_DEVICE_COMPILE__)
   extern __shared__ __attribute__((aligned(1024))) char smem_raw[];
   lds_char_ptr smem = (lds_char_ptr)smem_raw;
   if (gate_closed(gate)) return;
@@ -946,6 +960,7 @@ k_sweep(const bf16_t* __restrict__ Wp, const bf16_t* __restrict__ Hp_panel, int 
   // Gp: rows = tokens (n), k = vocabulary (m), straight from the registers (last: it consumes pk,
   // and its stores drain after the workgroup has gone)
   store_nm_packed_direct<C>(pk, Gp + (int64_t)nt * g_n_kt * (C::STAGE_B / 2), m0 / kPackK);
+#endif
 }
 
 // ---------------------------------------------------------------------------
@@ -958,6 +973,7 @@ k_bwd_dh(const bf16_t* __restrict__ WTp, int wt_n_kt, const bf16_t* __restrict__
          int64_t n_valid, int nk /* k-blocks to contract: ceil(V / 64) */,
          const float* __restrict__ row_factor /* f_t, panel-local */, bf16_t* __restrict__ dH /* panel's first row */,
          Gate gate) {
+#if defined(__HIP_DEVICE_COMPILE__)
   extern __shared__ __attribute__((aligned(1024))) char smem_raw[];
   lds_char_ptr smem = (lds_char_ptr)smem_raw;
   if (gate_closed(gate)) return;
@@ -999,6 +1015,7 @@ k_bwd_dh(const bf16_t* __restrict__ WTp, int wt_n_kt, const bf16_t* __restrict__
     store_nm<C>(smem, dH + n0 * d + m0, d, n_valid - n0, (int64_t)d - m0, c);
     __syncthreads();
   }
+#endif
 }
 
 // fp32 tile -> dW[n][m] (row pitch d), overwritten or added to, straight from the accumulators.
@@ -1050,6 +1067,7 @@ __global__ void __launch_bounds__(C::NT)
 k_bwd_dw(const bf16_t* __restrict__ HTp, const bf16_t* __restrict__ GTp, int t_n_kt /* strip pitch of both */, int d,
          int V, int nk /* k-blocks to contract: panel tokens / 64, rounded up to the tile */,
          float* __restrict__ dW, int accumulate, Gate gate) {
+#if defined(__HIP_DEVICE_COMPILE__)
   extern __shared__ __attribute__((aligned(1024))) char smem_raw[];
   lds_char_ptr smem = (lds_char_ptr)smem_raw;
   if (gate_closed(gate)) return;
@@ -1076,6 +1094,7 @@ k_bwd_dw(const bf16_t* __restrict__ HTp, const bf16_t* __restrict__ GTp, int t_n
 
   if (accumulate) store_dw_tile<C, true>(acc, dW, d, V, m0, n0);
   else store_dw_tile<C, false>(acc, dW, d, V, m0, n0);
+#endif
 }
 
 // ---------------------------------------------------------------------------

@@ -403,23 +403,36 @@ k_sweep_ref(const float2* __restrict__ sample, const float* __restrict__ zy, int
 }
 
 // Finishes one panel of the single sweep.  Per token row (panel-local index n, global t0 + n):
-//   S = sum of the vocabulary-tile partial sums (double, tile order),  lse = (ref2 + log2 S) ln 2,
+//   S = sum of the vocabulary-tile partial sums (double, fixed order),  lse = (ref2 + log2 S) ln 2,
 //   logprob = min(z_y - lse, 0),  diff = logprob - logq,  nis = -1 / S  (row factor of the gradient, times the
 //   correction below),
 // and patches the sampled token's entry of the unnormalised soft-max panel, in both packed
 // copies, to  Pt[y] - S = -S (1 - p_y)  (computed from expm1 so it is accurate when p_y -> 1).
 // Rows whose sum left the accepted range raise the fallback flag.
-__global__ void __launch_bounds__(256)
+constexpr int kFinishSlices = 8;
+constexpr int kFinishRows = 32;      // token rows per workgroup of kFinishSlices * kFinishRows threads
+__global__ void __launch_bounds__(kFinishSlices * kFinishRows)
 k_sweep_finish(const float* __restrict__ spart, int n_vt, int64_t ld_s, int64_t n_valid,
                const float* __restrict__ ref2, const float* __restrict__ zy, const float* __restrict__ logq,
                const int32_t* __restrict__ tokens, int V, float* __restrict__ logprob_out,
                double* __restrict__ diff, float* __restrict__ nis, bf16_t* __restrict__ Gp, int g_n_kt,
                bf16_t* __restrict__ GTp, int gt_n_kt, int* __restrict__ flag, Gate gate) {
   if (gate_closed(gate)) return;
-  const int64_t n = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (n >= n_valid) return;
-  double S = 0.0;
-  for (int mt = 0; mt < n_vt; ++mt) S += (double)spart[(int64_t)mt * ld_s + n];
+  // kFinishRows token rows per workgroup; the tile sums of a row are added in kFinishSlices interleaved slices
+  // (slice s takes tiles s, s + kFinishSlices, ...), then the slices in order: a fixed order, and
+  // enough workgroups to fill the chip with a panel's 12288 rows.
+  __shared__ double part[kFinishSlices][kFinishRows];
+  const int col = threadIdx.x % kFinishRows, slice = threadIdx.x / kFinishRows;
+  const int64_t n = (int64_t)blockIdx.x * kFinishRows + col;
+  double acc = 0.0;
+  if (n < n_valid)
+    for (int mt = slice; mt < n_vt; mt += kFinishSlices) acc += (double)spart[(int64_t)mt * ld_s + n];
+  part[slice][col] = acc;
+  __syncthreads();
+  if (slice != 0 || n >= n_valid) return;
+  double S = part[0][col];
+#pragma unroll
+  for (int s = 1; s < kFinishSlices; ++s) S += part[s][col];
   if (!(S <= (double)kSweepLimit)) atomicCAS(flag, 0, 1);     // also catches inf and NaN
   const double lse = ((double)ref2[n] + log2(S)) * kLn2;
   double lp = (double)zy[n] - lse;     // NaN if the token was out of range
