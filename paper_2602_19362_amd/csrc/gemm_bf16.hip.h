@@ -193,8 +193,24 @@ struct Mainloop {
   __device__ __forceinline__ void start(lds_char_ptr smem) { issue(0, smem, 0); }
 
   // k-blocks [k0, k1) of a tile with nk k-blocks in all (k0 even, after start() or an earlier steps()).
+  // PRELOADED (with k0 = 0): k-block 1 was issued beforehand as well (start(), then issue(1, smem, 1) if the tile
+  // has two blocks), by a caller whose work between two tiles leaves the LDS alone.  The first block then waits
+  // for its own loads only (loads return in order: once at most the second block's are outstanding the first
+  // has landed) and issues nothing.
+  template <bool PRELOADED = false>
   __device__ __forceinline__ void steps(lds_char_ptr smem, int k0, int k1, int nk, f32x16 (&acc)[C::TM][C::TN]) {
     int kt = k0;
+    if (PRELOADED) {
+      if (nk > 1) __builtin_amdgcn_s_waitcnt(vmcnt_imm(C::NI_A + C::NI_B));
+      else __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+      __syncthreads();
+      compute(0, smem, acc);
+      kt = 1;
+      if (kt < k1) {
+        step(1, smem, 1, nk, acc);
+        kt = 2;
+      }
+    }
     for (; kt + 2 <= k1; kt += 2) {
       step(0, smem, kt, nk, acc);
       step(1, smem, kt + 1, nk, acc);
@@ -204,8 +220,9 @@ struct Mainloop {
 
   // acc += A_tile * B_tile^T over k-blocks [0, nk) after start().  Ends with a barrier: on return
   // every wave is done reading LDS, so the caller may reuse it (or start() the next tile) at once.
+  template <bool PRELOADED = false>
   __device__ __forceinline__ void finish(lds_char_ptr smem, int nk, f32x16 (&acc)[C::TM][C::TN]) {
-    steps(smem, 0, nk, nk, acc);
+    steps<PRELOADED>(smem, 0, nk, nk, acc);
     __syncthreads();
   }
 };
@@ -541,14 +558,16 @@ k_fwd_lse(const bf16_t* __restrict__ Wp, const bf16_t* __restrict__ Hp, int V, i
   if (mt_begin < mt_end) {
     ml.set_a(Wp + mt_begin * strip_a, n_kt);
     ml.start(smem);
+    if (n_kt > 1) ml.issue(1, smem, 1);
   }
   for (int mt = mt_begin; mt < mt_end; ++mt) {
     const int m0 = mt * C::BM;
     zero_acc<C>(acc);
-    ml.finish(smem, n_kt, acc);
+    ml.template finish<true>(smem, n_kt, acc);
     if (mt + 1 < mt_end) {  // the epilogue below works in registers only: overlap it with the next tile's first loads
       ml.set_a(Wp + (mt + 1) * strip_a, n_kt);
       ml.start(smem);
+      if (n_kt > 1) ml.issue(1, smem, 1);
     }
 
     if (m0 + C::BM > V) {  // ragged last vocabulary tile: rows >= V do not exist (their logits are 0, not -inf)
