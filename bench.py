@@ -212,6 +212,11 @@ def main():
     status = oapl.read_device_status(ws)
     two_pass = bool(backward and oapl.took_two_passes(ws))
     loss = float(res.loss.item()) if args.path in ("loss", "grpo") else float(res[0].double().sum().item())
+    # exact integer sums of the inputs' bit patterns: two runs that print the same digest computed on the same data
+    inputs_digest = [int(batch.H.view(torch.int16).sum(dtype=torch.int64).item()),
+                     int(batch.W.view(torch.int16).sum(dtype=torch.int64).item()),
+                     int(batch.tokens.sum(dtype=torch.int64).item()),
+                     int(batch.logq.view(torch.int32).sum(dtype=torch.int64).item())]
     if args.calibration_copy:
         x = torch.ones(1 << 28, dtype=torch.float32, device=dev)
         y = torch.empty_like(x)
@@ -266,6 +271,7 @@ def main():
         "workspace_bytes": ws_bytes, "panel_rows": panel_rows if backward else None,
         "panel_buffers": panel_buffers if backward else None, "longest_rollout": longest,
         "kernels": kernels, "roofline": roofline, "loss" if args.path in ("loss", "grpo") else "output_checksum": loss,
+        "inputs_digest": inputs_digest,
     }
     if args.hidden_scale != 1.0:
         out["power_probe"] = f"hidden states scaled by {args.hidden_scale}: not the benchmark workload"

@@ -57,7 +57,7 @@ struct TileCfg {
   static constexpr int ROW_BYTES = kPackRowBytes;
   static constexpr int STAGE_A = BM * ROW_BYTES;   // one stage of the m-side operand
   static constexpr int STAGE_B = BN * ROW_BYTES;   // ... of the n-side operand
-  static constexpr int B_OFF = NS * STAGE_A;
+  static constexpr int SLOT = STAGE_A + STAGE_B;   // one ring slot: the m-side block, then the n-side block
   static constexpr int MAIN_BYTES = NS * (STAGE_A + STAGE_B);
   static constexpr int NI_A = BM / (8 * NW);    // direct loads per wave and stage (8 rows each), m-side operand
   static constexpr int NI_B = BN / (8 * NW);    // ... n-side operand
@@ -105,7 +105,11 @@ struct Mainloop {
 
   __amdgpu_buffer_rsrc_t ra, rb;
   int voff;                           // per-lane byte offset of this lane's chunk inside the first 8 rows a wave loads
-  int rdA[C::KSTEPS], rdB[C::KSTEPS]; // LDS byte offsets of this lane's operand fragment per k-step
+  // LDS byte offsets of this lane's operand fragments at k-step 0 of ring slot 0.  K-step ks sits at the
+  // same offset with address bits 5..6 flipped by ks (the swizzle is an XOR on the 16-byte chunk index and
+  // the k-step is bits 1..2 of that index); deriving it where it is used costs one XOR per operand and
+  // k-step and saves six registers over a table.
+  int rdA0, rdB0;
   int wave, lane;
 
   __device__ __forceinline__ void setup() {
@@ -125,12 +129,16 @@ struct Mainloop {
     }
     const int rowA = wm * C::TM * 32 + (lane & 31);
     const int rowB = wn * C::TN * 32 + (lane & 31);
-#pragma unroll
-    for (int ks = 0; ks < C::KSTEPS; ++ks) {
-      const int c = 2 * ks + (lane >> 5);
-      rdA[ks] = rowA * C::ROW_BYTES + ((c ^ swz(rowA)) << 4);
-      rdB[ks] = C::B_OFF + rowB * C::ROW_BYTES + ((c ^ swz(rowB)) << 4);
-    }
+    static_assert(C::KSTEPS == 4, "k-step index = chunk bits 1..2");
+    const int c0 = lane >> 5;
+    rdA0 = rowA * C::ROW_BYTES + ((c0 ^ swz(rowA)) << 4);
+    rdB0 = C::STAGE_A + rowB * C::ROW_BYTES + ((c0 ^ swz(rowB)) << 4);
+  }
+
+  // The empty asm keeps the compiler from hoisting the per-k-step addresses out of the loop (back into a table).
+  static __device__ __forceinline__ int fresh(int x) {
+    asm volatile("" : "+v"(x));
+    return x;
   }
 
   // Operand = one row-tile strip of a packed matrix: n_kt consecutive blocks of 32 KiB (A) / 48 KiB (B).
@@ -147,12 +155,12 @@ struct Mainloop {
 #pragma unroll
     for (int i = 0; i < C::NI_A; ++i)
       __builtin_amdgcn_raw_ptr_buffer_load_lds(
-          ra, (lds_void_ptr)(smem + STAGE * C::STAGE_A + (i * C::NW + wave) * 1024), 16, voff,
+          ra, (lds_void_ptr)(smem + STAGE * C::SLOT + (i * C::NW + wave) * 1024), 16, voff,
           kt * C::STAGE_A + i * C::NW * 1024, 0, 0);
 #pragma unroll
     for (int i = 0; i < C::NI_B; ++i)
       __builtin_amdgcn_raw_ptr_buffer_load_lds(
-          rb, (lds_void_ptr)(smem + C::B_OFF + STAGE * C::STAGE_B + (i * C::NW + wave) * 1024), 16, voff,
+          rb, (lds_void_ptr)(smem + STAGE * C::SLOT + C::STAGE_A + (i * C::NW + wave) * 1024), 16, voff,
           kt * C::STAGE_B + i * C::NW * 1024, 0, 0);
   }
 
@@ -160,12 +168,13 @@ struct Mainloop {
 #pragma unroll
     for (int ks = 0; ks < C::KSTEPS; ++ks) {
       bf16x8 a[C::TM], b[C::TN];
+      const int ra_ks = fresh(rdA0) ^ (ks << 5), rb_ks = fresh(rdB0) ^ (ks << 5);
 #pragma unroll
       for (int i = 0; i < C::TM; ++i)
-        a[i] = *(const __attribute__((address_space(3))) bf16x8*)(smem + STAGE * C::STAGE_A + rdA[ks] + i * 32 * C::ROW_BYTES);
+        a[i] = *(const __attribute__((address_space(3))) bf16x8*)(smem + STAGE * C::SLOT + ra_ks + i * 32 * C::ROW_BYTES);
 #pragma unroll
       for (int j = 0; j < C::TN; ++j)
-        b[j] = *(const __attribute__((address_space(3))) bf16x8*)(smem + STAGE * C::STAGE_B + rdB[ks] + j * 32 * C::ROW_BYTES);
+        b[j] = *(const __attribute__((address_space(3))) bf16x8*)(smem + STAGE * C::SLOT + rb_ks + j * 32 * C::ROW_BYTES);
       // all reads of a k-step are issued before its first multiplication; the scheduler then overlaps
       // them with the previous k-step's last multiplications instead of starting every k-step by waiting
       __builtin_amdgcn_sched_barrier(0);
@@ -695,14 +704,16 @@ k_fwd_sample(const bf16_t* __restrict__ Wp, const bf16_t* __restrict__ Hp, int V
   if (mt_begin < mt_end) {
     ml.set_a(Wp + mt_begin * strip_a, n_kt);
     ml.start(smem);
+    if (n_kt > 1) ml.issue(1, smem, 1);
   }
   for (int mt = mt_begin; mt < mt_end; ++mt) {
     const int m0 = mt * C::BM;
     zero_acc<C>(acc);
-    ml.finish(smem, n_kt, acc);
+    ml.template finish<true>(smem, n_kt, acc);
     if (mt + 1 < mt_end) {
       ml.set_a(Wp + (mt + 1) * strip_a, n_kt);
       ml.start(smem);
+      if (n_kt > 1) ml.issue(1, smem, 1);
     }
     const int row0 = m0 + wm * C::TM * 32 + 4 * h;
 #pragma unroll
