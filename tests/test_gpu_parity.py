@@ -446,6 +446,40 @@ def test_runs_are_bit_reproducible():
         assert torch.equal(a, c)
 
 
+@pytest.mark.parametrize("dtype,d,V,lens,cap", [
+    ("bf16", 320, 1544, [300, 17, 0, 383, 200, 100], 384),      # three panels, ragged token and vocabulary tiles
+    ("bf16", 64, 520, [5000, 13000, 1, 0, 9000], 0),             # three default panels, a rollout across two of them
+    ("f32", 72, 1000, [0, 1, 37, 64, 0, 129, 5, 64], 100),
+])
+def test_results_do_not_depend_on_what_the_buffers_held(dtype, d, V, lens, cap):
+    """The workspace and the outputs are written before they are read: the same call on buffers full of zeros,
+    of 0xFF bytes (NaN patterns) and of 0x3C bytes (finite numbers) gives the same bits, OAPL and GRPO."""
+    b = _custom_batch(dtype, d=d, V=V, lens=lens, n_groups=2, seed=44, beta=0.7, noise=0.05)
+    code = oapl.OAPL_BF16 if dtype == "bf16" else oapl.OAPL_F32
+    nbytes, _, _ = oapl.workspace_bytes_for(b.T, d, V, len(lens), 2, code, True, cap, max(lens))
+    ws = torch.empty(nbytes, dtype=torch.uint8, device=DEV)
+    dH = torch.empty_like(b.H)
+    dW = torch.empty(V, d, dtype=torch.float32, device=DEV)
+    logq, logp_old = _grpo_inputs(b, 5)
+    first = None
+    for fill in (0x00, 0xFF, 0x3C):
+        ws.fill_(fill)
+        dH.view(torch.uint8).fill_(fill)
+        dW.view(torch.uint8).fill_(fill)
+        res = _run(b, workspace=ws, dH=dH, dW=dW)
+        out = [t.clone() for t in (res.loss, res.logprob, res.seq_logratio, res.vstar, res.dH, res.dW)]
+        ws.fill_(fill)
+        g = _grpo(b.H, b.W, b.tokens, logq, logp_old, b.seq_offsets, b.rewards, b.group_ids, 2, workspace=ws,
+                  dH=dH, dW=dW)
+        torch.cuda.synchronize()
+        out += [t.clone() for t in (g.loss, g.logprob, g.dH, g.dW)]
+        if first is None:
+            first = out
+        else:
+            for a, c in zip(first, out):
+                assert torch.equal(a.view(torch.uint8), c.view(torch.uint8)), f"fill {fill:#x}"
+
+
 def test_device_side_errors_are_reported_not_faulted():
     b = _custom_batch("bf16", d=64, V=300, lens=[40, 24], n_groups=2, seed=11, beta=1.0)
     good = _run(b)
