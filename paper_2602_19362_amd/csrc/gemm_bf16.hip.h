@@ -203,15 +203,14 @@ struct Mainloop {
 
   // k-blocks [k0, k1) of a tile with nk k-blocks in all (k0 even, after start() or an earlier steps()).
   // PRELOADED (with k0 = 0): k-block 1 was issued beforehand as well (start(), then issue(1, smem, 1) if the tile
-  // has two blocks), by a caller whose work between two tiles leaves the LDS alone.  The first block then waits
-  // for its own loads only (loads return in order: once at most the second block's are outstanding the first
-  // has landed) and issues nothing.
+  // has two blocks), by a caller whose work between two tiles leaves the LDS alone.  The first block then issues
+  // nothing.  It waits for both blocks: waiting for the first alone (vmcnt = the second block's loads, and a bare
+  // s_barrier, since __syncthreads() waits for every outstanding load itself) measured no different.
   template <bool PRELOADED = false>
   __device__ __forceinline__ void steps(lds_char_ptr smem, int k0, int k1, int nk, f32x16 (&acc)[C::TM][C::TN]) {
     int kt = k0;
     if (PRELOADED) {
-      if (nk > 1) __builtin_amdgcn_s_waitcnt(vmcnt_imm(C::NI_A + C::NI_B));
-      else __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+      __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
       __syncthreads();
       compute(0, smem, acc);
       kt = 1;
