@@ -1148,43 +1148,66 @@ k_pack_rows(const bf16_t* __restrict__ src, int64_t R, int K, int64_t ld, bf16_t
   }
 }
 
-// dst = packed(S^T), an m-side operand (256-row blocks), where S [R, Ccols] is row-major (ld) and optionally row-scaled:
+// dst = packed(S^T), an m-side operand (256-row blocks), where S [R, Ccols] is row-major (ld; Ccols and ld
+// multiples of 8, rows 16-byte aligned) and optionally row-scaled:
 // dst row j (a column of S), k index r (a row of S): dst(j, r) = bf16(S[r][j] * scale[r]).
-// One workgroup per destination block (jt, kt): it reads S[kt*64 .. +64][jt*256 .. +256]
-// through LDS.  Blocks in [0, n_jt) x [0, n_kt); zero outside [0, Ccols) x [0, R).
+// One workgroup per destination block (jt, kt): it reads S[kt*64 .. +64][jt*256 .. +256] in 16-byte
+// pieces (8 columns of one row), four consecutive rows per thread, turns each 4 x 8 patch into eight
+// 8-byte column pieces (4 rows of one column) and parks them in LDS as [row quad][column]; a
+// destination chunk (8 consecutive r of one j, 16 bytes) is then two 8-byte LDS reads.
+// Blocks in [0, n_jt) x [0, n_kt); zero outside [0, Ccols) x [0, R).
 __global__ void __launch_bounds__(256)
 k_pack_transposed(const bf16_t* __restrict__ src, int64_t R, int Ccols, int64_t ld, const float* __restrict__ scale,
                   bf16_t* __restrict__ dst, int n_kt, Gate gate) {
-  __shared__ bf16_t tile[64][kPackRowsA + 2];
+  constexpr int kPitch = kPackRowsA * 8 + 16;     // bytes per row quad: 256 columns x 8 bytes; +16 keeps the reads below off each other's banks
+  __shared__ __attribute__((aligned(16))) char tile[(kPackK / 4) * kPitch];
   if (gate_closed(gate)) return;
   const int kt = blockIdx.x, jt = blockIdx.y;
   const int64_t r0 = (int64_t)kt * kPackK;
   const int j0 = jt * kPackRowsA;
-  for (int i = threadIdx.x >> 6; i < 64; i += 4) {          // 4 source rows per pass, 64 lanes x 4 columns each
-    const int64_t r = r0 + i;
-    const float sc = (scale != nullptr && r < R) ? scale[r] : 1.f;
+  const int cc = threadIdx.x & 31;                // 8-column piece of the 256 columns
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      const int jl = (threadIdx.x & 63) + q * 64;
-      const int j = j0 + jl;
-      bf16_t v = (bf16_t)0.f;
+  for (int pass = 0; pass < 2; ++pass) {
+    const int rq = (threadIdx.x >> 5) + 8 * pass;   // row quad 0 .. 15
+    const int j = j0 + cc * 8;
+    u32x4 row[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const int64_t r = r0 + 4 * rq + k;
+      row[k] = u32x4{0u, 0u, 0u, 0u};
       if (r < R && j < Ccols) {
-        v = src[r * ld + j];
-        if (scale != nullptr) v = (bf16_t)((float)v * sc);
+        row[k] = *(const u32x4*)(src + r * ld + j);
+        if (scale != nullptr) {
+          const float sc = scale[r];
+#pragma unroll
+          for (int m = 0; m < 4; ++m) {
+            const uint32_t x = row[k][m];   // a copy: a vector element is not an object whose bytes can be reinterpreted in place
+            const bf16x2 v = __builtin_bit_cast(bf16x2, x);
+            const bf16x2 w = {(bf16_t)((float)v[0] * sc), (bf16_t)((float)v[1] * sc)};
+            row[k][m] = __builtin_bit_cast(uint32_t, w);
+          }
+        }
       }
-      tile[i][jl] = v;
+    }
+    // dword m of a row holds columns 2m (low half) and 2m + 1 (high half)
+    char* out = tile + rq * kPitch + cc * 64;
+#pragma unroll
+    for (int m = 0; m < 4; ++m) {
+      const uint32_t a0 = row[0][m], a1 = row[1][m], a2 = row[2][m], a3 = row[3][m];
+      const u32x4 piece = {(a0 & 0xFFFFu) | (a1 << 16), (a2 & 0xFFFFu) | (a3 << 16),        // column 2m: rows 0..3
+                           (a0 >> 16) | (a1 & 0xFFFF0000u), (a2 >> 16) | (a3 & 0xFFFF0000u)};  // column 2m + 1
+      *(u32x4*)(out + m * 16) = piece;
     }
   }
   __syncthreads();
-  char* out = (char*)dst + ((int64_t)jt * n_kt + kt) * (int64_t)kPackBlockBytesA;
+  char* outb = (char*)dst + ((int64_t)jt * n_kt + kt) * (int64_t)kPackBlockBytesA;
 #pragma unroll
   for (int it = 0; it < 8; ++it) {
     const int idx = it * 256 + threadIdx.x;
-    const int row = idx >> 3, c = idx & 7;                  // destination row (j), 8 consecutive k
-    bf16x8 v;
-#pragma unroll
-    for (int e = 0; e < 8; ++e) v[e] = tile[c * 8 + e][row];
-    *(bf16x8*)(out + row * 128 + c * 16) = v;
+    const int rowj = idx >> 3, c = idx & 7;                 // destination row (j), 8 consecutive k = row quads 2c, 2c + 1
+    const u32x2 lo = *(const u32x2*)(tile + (2 * c) * kPitch + rowj * 8);
+    const u32x2 hi = *(const u32x2*)(tile + (2 * c + 1) * kPitch + rowj * 8);
+    *(u32x4*)(outb + rowj * 128 + c * 16) = u32x4{lo[0], lo[1], hi[0], hi[1]};
   }
 }
 
