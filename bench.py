@@ -30,11 +30,11 @@ PEAK_BF16_TFLOPS = 2516.6     # MI355X dense bf16 MFMA: 256 CU x 4096 flop/clk x
 # sources at run time and the figure is reported as null when they differ.
 TRAFFIC = {
     "workload": "qwen7b",
-    "sources_sha256_16": "03ad620ed0740596",
+    "sources_sha256_16": "1e30c9e65a5b3746",
     "per_launch_bytes": {          # averages over the step's 12 panels (11 of 12288 rows, one of 5729)
-        "k_sweep": {"read": 18.13e9, "write": 7.17e9},
-        "k_bwd_dh": {"read": 16.83e9, "write": 0.10e9},
-        "k_bwd_dw": {"read": 19.01e9, "write": 2.49e9},
+        "k_sweep": {"read": 17.34e9, "write": 7.17e9},
+        "k_bwd_dh": {"read": 16.84e9, "write": 0.10e9},
+        "k_bwd_dw": {"read": 19.40e9, "write": 2.49e9},
     },
 }
 

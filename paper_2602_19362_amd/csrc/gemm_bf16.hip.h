@@ -1159,7 +1159,8 @@ k_pack_rows(const bf16_t* __restrict__ src, int64_t R, int K, int64_t ld, bf16_t
 __global__ void __launch_bounds__(256)
 k_pack_transposed(const bf16_t* __restrict__ src, int64_t R, int Ccols, int64_t ld, const float* __restrict__ scale,
                   bf16_t* __restrict__ dst, int n_kt, Gate gate) {
-  constexpr int kPitch = kPackRowsA * 8 + 16;     // bytes per row quad: 256 columns x 8 bytes; +16 keeps the reads below off each other's banks
+  // bytes per row quad: 256 columns x 8 bytes; +16 keeps the reads below off each other's banks
+  constexpr int kPitch = kPackRowsA * 8 + 16;
   __shared__ __attribute__((aligned(16))) char tile[(kPackK / 4) * kPitch];
   if (gate_closed(gate)) return;
   const int kt = blockIdx.x, jt = blockIdx.y;
@@ -1181,7 +1182,8 @@ k_pack_transposed(const bf16_t* __restrict__ src, int64_t R, int Ccols, int64_t 
           const float sc = scale[r];
 #pragma unroll
           for (int m = 0; m < 4; ++m) {
-            const uint32_t x = row[k][m];   // a copy: a vector element is not an object whose bytes can be reinterpreted in place
+            // a copy: a vector element is not an object whose bytes can be reinterpreted in place
+            const uint32_t x = row[k][m];
             const bf16x2 v = __builtin_bit_cast(bf16x2, x);
             const bf16x2 w = {(bf16_t)((float)v[0] * sc), (bf16_t)((float)v[1] * sc)};
             row[k][m] = __builtin_bit_cast(uint32_t, w);

@@ -505,9 +505,10 @@ static int sweep_path(const Plan& p, const void* H, const void* W, const int32_t
           p.n_kt_t, spart, p.Tp, fast);
     }
     OAPL_LAUNCH_CHECK();
-    k_sweep_finish<<<grid1d(nv, kFinishRows), kFinishSlices * kFinishRows, 0, st>>>(spart, MTv, p.Tp, nv, ref2 + t0, zy + t0, logq + t0, tokens + t0,
-                                                    V, logprob_out ? logprob_out + t0 : nullptr, diff + t0, nis + t0,
-                                                    Gbuf(k), p.n_kt_g, GTbuf(k), p.n_kt_t, flag, fast);
+    k_sweep_finish<<<grid1d(nv, kFinishRows), kFinishSlices * kFinishRows, 0, st>>>(
+        spart, MTv, p.Tp, nv, ref2 + t0, zy + t0, logq + t0, tokens + t0, V,
+        logprob_out ? logprob_out + t0 : nullptr, diff + t0, nis + t0, Gbuf(k), p.n_kt_g, GTbuf(k), p.n_kt_t, flag,
+        fast);
     OAPL_LAUNCH_CHECK();
     if (k >= p.n_buf - 1 && p.n_buf > 1)
       if (int rc = gradients(k - (p.n_buf - 1))) return rc;
